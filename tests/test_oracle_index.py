@@ -1,0 +1,254 @@
+"""Pins for index selection (Alg. 2 TopK / CombineIndices, Alg. 3 TopKBlocks,
+the per-head pattern rule and the default budgets)."""
+import itertools
+
+import numpy as np
+import pytest
+from hypothesis import given, settings, strategies as st
+
+from harness import gen
+from oracle import oracle as orc
+
+T, IS, BC = 0, 1, 2
+
+
+def _bud(**kw):
+    d = dict(sink_blocks=1, local_blocks=1, k_vertical=3, k_slash=2, k_blocks=13)
+    d.update(kw)
+    return orc.Budgets(**d)
+
+
+def _brute_topk(score, k):
+    """Lexicographically smallest index set among those of maximal total score."""
+    best, best_sum = None, None
+    sc = [float(x) for x in score]          # fp32 values: sums of a few are exact in fp64
+    for comb in itertools.combinations(range(len(sc)), k):
+        t = sum(sc[c] for c in comb)
+        if best is None or t > best_sum:
+            best, best_sum = comb, t
+    return np.array(best, np.int32)
+
+
+def test_topk_brute_force_seq64():
+    # seq_len 64 end to end: scores from the estimator, all three selections by enumeration
+    N, b, w = 64, 8, 8
+    Q, K, _ = gen.random_qkv(2, 1, N, 128, seed=64)
+    v, s, blk = (x.astype(np.float32) for x in orc.estimate(Q, K, b, w))
+    nb = N // b
+    bud = _bud(k_vertical=3, k_slash=2, k_blocks=nb + 4)
+    for h in range(2):
+        ix = orc.build_index(v, s, blk, N, b, w, bud, override=[IS, IS])
+        assert (ix.cols[h] == _brute_topk(v[h], 3)).all()
+        assert (ix.offs[h] == _brute_topk(s[h], 2)).all()
+        ix = orc.build_index(v, s, blk, N, b, w, bud, override=[BC, BC])
+        cand = [(R, C) for R in range(nb) for C in range(R)]
+        sel = _brute_topk([blk[h, R, C] for R, C in cand], 4)
+        want = {cand[t] for t in sel} | {(R, R) for R in range(nb)}
+        got = {(R, int(C)) for R in range(nb)
+               for C in ix.blkcols[h, ix.rowptr[h, R]:ix.rowptr[h, R + 1]]}
+        assert got == want
+
+
+def _stable_topk(score, k):
+    bits = np.asarray(score, np.float32).view(np.uint32).astype(np.int64)
+    return np.sort(np.argsort(-bits, kind="stable")[:k]).astype(np.int32)
+
+
+@settings(max_examples=60, deadline=None)
+@given(st.lists(st.integers(0, 4), min_size=16, max_size=16), st.integers(1, 7),
+       st.lists(st.integers(0, 3), min_size=16, max_size=16), st.integers(1, 5))
+def test_topk_ties_go_to_lower_index(vs, kv, ss, ks):
+    N, b, w = 16, 4, 4
+    v = np.array([vs], np.float32)
+    s = np.array([ss], np.float32)
+    blk = np.zeros((1, 4, 4), np.float32)
+    ix = orc.build_index(v, s, blk, N, b, w, _bud(k_vertical=kv, k_slash=ks, k_blocks=4),
+                         override=[IS])
+    assert (ix.cols[0] == _stable_topk(v[0], kv)).all()
+    assert (ix.offs[0] == _stable_topk(s[0], ks)).all()
+    if kv <= 4:
+        assert (ix.cols[0] == _brute_topk(v[0], kv)).all()
+
+
+@settings(max_examples=40, deadline=None)
+@given(st.lists(st.integers(0, 3), min_size=36, max_size=36), st.integers(6, 21))
+def test_block_topk_ties_and_csr_invariants(vals, kb):
+    nb, b = 6, 4
+    N = nb * b
+    blk = np.array(vals, np.float32).reshape(1, nb, nb)
+    v = np.ones((1, N), np.float32)
+    ix = orc.build_index(v, v, blk, N, b, 4, _bud(k_blocks=kb), override=[BC])
+    cand = [(R, C) for R in range(nb) for C in range(R)]
+    flat = np.array([R * nb + C for R, C in cand])
+    sel = _stable_topk([blk[0, R, C] for R, C in cand], kb - nb)
+    want = sorted(list(flat[sel]) + [R * nb + R for R in range(nb)])
+    rp = ix.rowptr[0]
+    got = [R * nb + int(C) for R in range(nb) for C in ix.blkcols[0, rp[R]:rp[R + 1]]]
+    assert got == want
+    assert rp[0] == 0 and (np.diff(rp) >= 1).all() and rp[nb] == len(want) == kb
+    for R in range(nb):
+        row = ix.blkcols[0, rp[R]:rp[R + 1]]
+        assert (np.diff(row) > 0).all() and row[-1] == R
+    assert (ix.blkcols[0, rp[nb]:] == -1).all()
+
+
+def test_k_larger_than_candidates_is_clamped():
+    N, b = 16, 4
+    v = np.arange(16, dtype=np.float32)[None]
+    blk = np.random.default_rng(0).random((1, 4, 4)).astype(np.float32)
+    ix = orc.build_index(v, v, blk, N, b, 4, _bud(k_vertical=20, k_slash=18, k_blocks=30),
+                         override=[IS])
+    assert ix.n_cols[0] == 16 and (ix.cols[0, :16] == np.arange(16)).all() and (ix.cols[0, 16:] == -1).all()
+    assert ix.n_offs[0] == 16
+    ix = orc.build_index(v, v, blk, N, b, 4, _bud(k_blocks=30), override=[BC])
+    assert ix.rowptr[0, -1] == 10                 # all causal blocks
+
+
+def test_triangular_csr_matches_definition():
+    N, b = 40 * 8, 8
+    nb = N // b
+    v = np.ones((1, N), np.float32)
+    bud = _bud(sink_blocks=2, local_blocks=5, k_blocks=10)
+    ix = orc.build_index(v, v, np.zeros((1, nb, nb), np.float32), N, b, 8, bud, override=[T])
+    R, C = np.tril_indices(nb)
+    keep = (C < 2) | (R - C < 5)
+    assert ix.rowptr[0, -1] == keep.sum() == orc.triangular_count(nb, 2, 5)
+    got = [(r, int(c)) for r in range(nb) for c in ix.blkcols[0, ix.rowptr[0, r]:ix.rowptr[0, r + 1]]]
+    assert got == sorted(zip(R[keep].tolist(), C[keep].tolist()))
+    assert ix.n_cols[0] == 0 and ix.n_offs[0] == 0 and (ix.cols == -1).all()
+
+
+# ---- default budgets: the values of the benchmark definition's five shapes
+
+@pytest.mark.parametrize("N,b,rho,want", [
+    (4096, 64, 0.10, (208, 2, 128, 3)),
+    (16384, 64, 0.125, (4112, 15, 512, 16)),
+    (32768, 64, 0.06, (7880, 14, 512, 15)),
+    (65536, 128, 0.04, (5253, 9, 640, 20)),
+    (131072, 128, 0.03, (15744, 14, 960, 31)),
+])
+def test_default_budgets_table(N, b, rho, want):
+    bud = orc.default_budgets(N, b, rho)
+    assert (bud.k_blocks, bud.local_blocks, bud.k_vertical, bud.k_slash) == want
+    nb = N // b
+    # L is the largest band that fits: the real block count fits, one more does not
+    assert orc.triangular_count(nb, bud.sink_blocks, bud.local_blocks) <= bud.k_blocks
+    L1 = bud.local_blocks + 1
+    assert L1 * nb - L1 * (L1 - 1) // 2 + (nb - L1) * bud.sink_blocks > bud.k_blocks
+
+
+# ---- pattern rule: decided cases and the exact boundary
+
+def _fx(x):
+    return int(np.floor(float(np.float32(x)) * 2.0 ** 30))
+
+
+def _rule_bigint(v, s, N, b, w, bud):
+    nb = N // b
+    sb = min(bud.sink_blocks * b, N)
+    lb0 = max((nb - bud.local_blocks) * b, sb)
+    Vtot = sum(_fx(x) for x in v)
+    CT = sum(_fx(x) for j, x in enumerate(v) if j < sb or j >= lb0)
+    E = sum(N - w + i + 1 for i in range(w))
+    ET = sum(min(sb, N - w + i + 1) + max(0, N - w + i + 1 - lb0) for i in range(w))
+    if bud.lift_den * CT * E >= bud.lift_num * Vtot * ET:
+        return T
+    top = lambda a, k: sum(sorted((_fx(x) for x in a), reverse=True)[:k])
+    if bud.lift_den * (top(v, bud.probe_v) + top(s, bud.probe_s)) * E >= \
+            bud.lift_num * Vtot * (bud.probe_v + bud.probe_s) * w:
+        return IS
+    return BC
+
+
+def test_pattern_rule_decided_cases():
+    N, b, w = 1024, 64, 64
+    bud = _bud(sink_blocks=1, local_blocks=2)
+    inv = 1.0 / (np.arange(N - w, N) + 1.0)
+    uni = np.array([inv[max(0, j - (N - w)):].sum() for j in range(N)], np.float32)
+    assert orc.choose_pattern(uni, uni, N, b, w, bud) == BC          # uniform head: lift 1
+    tri = np.zeros(N, np.float32); tri[:4] = 8.0; tri[N - 128:] = 0.25
+    assert orc.choose_pattern(tri, uni, N, b, w, bud) == T
+    col = uni.copy(); col[[100, 300, 500, 700]] = 6.0                 # four heavy columns, mid-sequence
+    assert orc.choose_pattern(col, uni, N, b, w, bud) == IS
+    sl = uni.copy(); sl[[7, 200]] = 20.0                              # two heavy diagonals
+    assert orc.choose_pattern(uni, sl, N, b, w, bud) == IS
+
+
+def test_pattern_rule_exact_boundary():
+    # choose masses so that lift_den*C_T*E == lift_num*Vtot*E_T exactly, then nudge one ulp
+    N, b, w = 256, 64, 64
+    bud = _bud(sink_blocks=1, local_blocks=1, lift_num=2, lift_den=1)
+    E = sum(N - w + i + 1 for i in range(w))
+    ET = sum(min(64, N - w + i + 1) + max(0, N - w + i + 1 - 192) for i in range(w))
+    # v: x on the 128 region keys, y elsewhere; need C_T*E == 2*Vtot*E_T
+    # C_T = 128x, Vtot = 128x + 128y  ->  x*(E - 2*ET) = 2*ET*y
+    x, y = 2 * ET, E - 2 * ET
+    scale = 2.0 ** -14
+    v = np.full(N, y * scale, np.float32); v[:64] = x * scale; v[192:] = x * scale
+    assert float(v[0]) == x * scale and float(v[100]) == y * scale
+    s = np.zeros(N, np.float32)
+    assert _rule_bigint(v, s, N, b, w, bud) == T
+    assert orc.choose_pattern(v, s, N, b, w, bud) == T                # equality counts as Triangular
+    v2 = v.copy(); v2[100] = np.nextafter(v2[100], np.float32(np.inf))
+    assert _rule_bigint(v2, s, N, b, w, bud) != T
+    assert orc.choose_pattern(v2, s, N, b, w, bud) == _rule_bigint(v2, s, N, b, w, bud)
+
+
+@settings(max_examples=30, deadline=None)
+@given(st.integers(0, 2 ** 31 - 1))
+def test_pattern_rule_matches_bigint(seed):
+    rng = np.random.default_rng(seed)
+    N, b, w = 128, 16, 16
+    v = (rng.random(N) ** 8 * 16).astype(np.float32)
+    s = (rng.random(N) ** 8 * 16).astype(np.float32)
+    bud = _bud(sink_blocks=1, local_blocks=int(rng.integers(1, 4)), lift_num=int(rng.integers(1, 6)))
+    assert orc.choose_pattern(v, s, N, b, w, bud) == _rule_bigint(v, s, N, b, w, bud)
+
+
+# ---- planted recovery: with k = planted counts the selected sets are the planted sets
+
+def _recover(wl):
+    data = gen.generate(wl)
+    N, b, w = wl.seq_len, wl.block, wl.last_q
+    v, s, blk = orc.estimate(data["Q"], data["K"], b, w)
+    return data, v.astype(np.float32), s.astype(np.float32), blk.astype(np.float32)
+
+
+def test_planted_recovery_cfg1():
+    wl = gen.WORKLOADS["cfg1"]
+    data, v, s, blk = _recover(wl)
+    bud = orc.default_budgets(wl.seq_len, wl.block, wl.keep)
+    bud.k_vertical, bud.k_slash = 4, 3
+    ix = orc.build_index(v, s, blk, wl.seq_len, wl.block, wl.last_q, bud,
+                         override=[IS] * wl.n_q_heads)
+    for h in range(wl.n_q_heads):
+        assert ix.cols[h].tolist() == [0, 1, 2, 3]
+        assert ix.offs[h].tolist() == [0, 64, 512]
+
+
+def test_planted_recovery_small_mixed():
+    # +3 logit plants against lognormal noise: a planted item always ranks inside the
+    # best 2k, and the hot blocks are inside the default block budget
+    # (one global top-k over raw block softmax values fills short early rows first)
+    wl = gen.scaled(gen.WORKLOADS["cfg3"], name="mini3", n_q_heads=8, n_kv_heads=2,
+                    seq_len=8192, seed=77, n_hot=12, keep=0.25)
+    data, v, s, blk = _recover(wl)
+    N, b, w = wl.seq_len, wl.block, wl.last_q
+    bud = orc.default_budgets(N, b, wl.keep)
+    bud.k_vertical, bud.k_slash = 2 * wl.n_cols, 2 * wl.n_offs
+    planted = [p.pattern for p in data["plants"]]
+    ix = orc.build_index(v, s, blk, N, b, w, bud, override=planted)
+    for h, p in enumerate(data["plants"]):
+        if p.pattern == IS:
+            assert set(p.cols.tolist()) <= set(ix.cols[h].tolist())
+            assert set(p.offs.tolist()) <= set(ix.offs[h].tolist())
+        if p.pattern == BC:
+            got = {(R, int(C)) for R in range(N // b)
+                   for C in ix.blkcols[h, ix.rowptr[h, R]:ix.rowptr[h, R + 1]] if C != R}
+            assert {(int(R), int(C)) for R, C in p.hot} <= got
+            assert len(got) == bud.k_blocks - N // b
+    # the run-time rule agrees with the plant on Triangular / Interval-Slash heads
+    auto = orc.build_index(v, s, blk, N, b, w, orc.default_budgets(N, b, wl.keep)).pattern
+    for h, p in enumerate(data["plants"]):
+        if p.pattern in (T, IS):
+            assert auto[h] == p.pattern
