@@ -1,0 +1,137 @@
+/*
+ * sa.h - C ABI of the MI355X (gfx950) dynamic sparse prefill attention library.
+ *
+ * One attention layer, batch 1, causal.  Per query head the library
+ *   1. scores a window of the last queries against all keys
+ *      (sa_estimate_patterns),
+ *   2. decides which sparsity pattern the head follows and selects its
+ *      columns, diagonals and blocks (sa_build_index),
+ *   3. runs causal softmax attention over the selected entries only
+ *      (sa_sparse_prefill).
+ *
+ * Conventions
+ *   - C99 types only.  Q, K, V, O are DEVICE pointers to raw bf16 (16-bit)
+ *     elements; O is written with round-to-nearest-even.
+ *   - The caller owns every device buffer (Q, K, V, O, scores, index,
+ *     workspace).  Sizes come from the *_bytes queries.  The library never
+ *     allocates or frees device memory and never synchronises the host: the
+ *     three compute calls enqueue kernels on the given HIP stream and return.
+ *   - Errors are return codes.  Argument checks are synchronous;
+ *     SA_ERR_HIP wraps a failed launch; sa_last_error gives a text.
+ *     Unsupported shapes are rejected, nothing is silently padded.
+ *   - Index arrays are plain int32 and canonical (ascending, -1 padded): two
+ *     index sets are equal iff their bytes are equal.  Same inputs give the
+ *     same bytes, run to run.
+ *   - A context serialises nothing: do not run two calls on one context
+ *     concurrently (they share its workspace).
+ */
+#ifndef SA_H_
+#define SA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct sa_ctx sa_ctx; /* opaque, host memory */
+
+typedef enum {
+  SA_OK = 0,
+  SA_ERR_INVALID_ARG = 1,
+  SA_ERR_UNSUPPORTED = 2,
+  SA_ERR_BUFFER_TOO_SMALL = 3,
+  SA_ERR_HIP = 4
+} sa_status;
+
+/* The three patterns named in the paper's contributions list. */
+typedef enum {
+  SA_PATTERN_AUTO = -1,
+  SA_TRIANGULAR = 0,     /* sink key blocks + local band (static) */
+  SA_INTERVAL_SLASH = 1, /* top vertical columns + top diagonals (Alg. 2) */
+  SA_BLOCK_CLUSTER = 2   /* top blocks of the block-mean map (Alg. 3) */
+} sa_pattern;
+
+typedef struct {
+  int32_t n_q_heads, n_kv_heads, head_dim; /* n_q_heads % n_kv_heads == 0, <= 128 heads; head_dim must be 128 */
+  int32_t seq_len, block, last_q;          /* seq_len % block == 0; block in {64,128}; 1 <= last_q <= 64 */
+  float softmax_scale;                     /* 0 => 1/sqrt(head_dim) */
+  int32_t sink_blocks, local_blocks;       /* Triangular: key blocks [0,sink) and the band R-C < local */
+  int32_t k_vertical, k_slash, k_blocks;   /* Alg. 2 k_v, k_s; Alg. 3 k_b (includes the forced diagonal blocks) */
+  int32_t probe_v, probe_s, lift_num, lift_den; /* pattern rule; 0 => defaults 4,4,4,1 */
+  int64_t q_head_stride, q_row_stride;     /* in elements; 0 => contiguous [H][N][d]; O uses Q's strides */
+  int64_t kv_head_stride, kv_row_stride;   /* K and V; row strides must be multiples of 8 elements */
+} sa_config;
+
+/* Device score buffers written by sa_estimate_patterns (Alg. 2 SumRows /
+ * SumDiagonals on the last-query window; Alg. 3 blocked attention map):
+ *   v   [n_q_heads][seq_len]   fp32  vertical score of key column j
+ *   s   [n_q_heads][seq_len]   fp32  slash score of diagonal offset o = i - j
+ *   blk [n_q_heads][nb][nb]    fp32  block map, nb = seq_len/block, entries C > R are 0 */
+typedef struct { float *v, *s, *blk; } sa_scores;
+
+/* Device index buffers written by sa_build_index, read by sa_sparse_prefill:
+ *   pattern [H]            chosen sa_pattern
+ *   n_cols  [H]            number of selected key columns
+ *   cols    [H][k_vertical] ascending, -1 padded
+ *   n_offs  [H]            number of selected diagonal offsets
+ *   offs    [H][k_slash]   ascending, -1 padded
+ *   rowptr  [H][nb+1]      block CSR row pointers
+ *   blkcols [H][cap]       key-block ids, ascending within a row, -1 padded;
+ *                          cap = sizes[6]/(4*H) from sa_index_bytes
+ * A query i attends key j <= i iff (i/block, j/block) is in the CSR, or j is
+ * in cols, or i-j is in offs (a union: each key counted once). */
+typedef struct { int32_t *pattern, *n_cols, *cols, *n_offs, *offs, *rowptr, *blkcols; } sa_index;
+
+/* Fill sink_blocks, local_blocks, k_vertical, k_slash, k_blocks from a keep
+ * fraction of the causal blocks (0 < keep <= 1).  seq_len and block must be
+ * set.  The paper leaves these budgets as inputs of Alg. 2 / Alg. 3. */
+sa_status sa_default_budgets(sa_config *cfg, double keep_fraction);
+
+/* Validate cfg and create a context (host memory only). */
+sa_status sa_create(const sa_config *cfg, sa_ctx **out);
+void sa_destroy(sa_ctx *ctx);
+
+/* Byte sizes of the three score buffers {v, s, blk}. */
+sa_status sa_scores_bytes(const sa_ctx *ctx, size_t v_s_blk[3]);
+/* Byte sizes of the seven index buffers, in sa_index member order. */
+sa_status sa_index_bytes(const sa_ctx *ctx, size_t sizes[7]);
+/* Device workspace the compute calls need; attach it before the first call.
+ * The pointer must be 256-byte aligned and stays owned by the caller. */
+sa_status sa_workspace_bytes(const sa_ctx *ctx, size_t *bytes);
+sa_status sa_set_workspace(sa_ctx *ctx, void *dev, size_t bytes);
+
+/* Alg. 2 "Compute Dense Attention Scores" + SumRows / SumDiagonals restricted
+ * to the last last_q query rows, and Alg. 3 "Compute Blocked Representation".
+ * Q [Hq][N][d], K [Hkv][N][d] bf16 device.  Writes all of out.v, out.s, out.blk. */
+sa_status sa_estimate_patterns(sa_ctx *ctx, const void *Q, const void *K, sa_scores out,
+                               void *hip_stream);
+
+/* Per-head pattern choice (Main Idea, "Categorization of Attention Heads") and
+ * Alg. 2 TopK / CombineIndices, Alg. 3 TopKBlocks.  Integer-exact: scores are
+ * compared by their fp32 bit patterns, ties go to the lower index.
+ * pattern_override_host: HOST array of n_q_heads sa_pattern values
+ * (SA_PATTERN_AUTO = decide), or NULL for all-auto.  Writes all of `out`. */
+sa_status sa_build_index(sa_ctx *ctx, sa_scores in, const int32_t *pattern_override_host,
+                         sa_index out, void *hip_stream);
+
+/* Alg. 2 / Alg. 3 "Compute Sparse Attention": O[h][i] = sum over the kept
+ * keys j of softmax_j(scale * Q_h[i].K[j]) V[j].  Q, O [Hq][N][d]; K, V
+ * [Hkv][N][d] bf16 device.  Any index in the documented layout is accepted,
+ * not only one produced by sa_build_index. */
+sa_status sa_sparse_prefill(sa_ctx *ctx, const void *Q, const void *K, const void *V,
+                            sa_index idx, void *O, void *hip_stream);
+
+/* Average duration in milliseconds of the kernels launched by the last compute
+ * call is not tracked here; time with HIP events on the stream you pass. */
+
+const char *sa_last_error(const sa_ctx *ctx);
+
+/* Library version string. */
+const char *sa_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SA_H_ */

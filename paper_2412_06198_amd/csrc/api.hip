@@ -1,0 +1,224 @@
+// Host side of the C ABI declared in include/sa.h: argument checks, shape
+// resolution, workspace carving, and the three launch sequences.
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "sa_internal.h"
+
+struct sa_ctx {
+  sa_config cfg;
+  sa::Shape sh;
+  sa::Workspace ws;
+  bool have_ws;
+  size_t ws_bytes;
+  size_t off[6];
+  char err[256];
+};
+
+namespace {
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+long long triangular_count(int nb, int sink, int local) {
+  long long n = 0;
+  for (int R = 0; R < nb; ++R) {
+    const int bs = R - local + 1 > 0 ? R - local + 1 : 0;
+    n += (sink < bs ? sink : bs) + (R - bs + 1);
+  }
+  return n;
+}
+
+sa_status fail(sa_ctx *c, sa_status st, const char *msg) {
+  if (c) snprintf(c->err, sizeof(c->err), "%s", msg);
+  return st;
+}
+
+void carve(sa_ctx *c) {
+  const sa::Shape &s = c->sh;
+  size_t o = 0;
+  c->off[0] = o; o += align256((size_t)s.Hq * s.nb * sa::kHeadDim * 4);
+  c->off[1] = o; o += align256((size_t)s.Hkv * s.nb * sa::kHeadDim * 4);
+  c->off[2] = o; o += align256((size_t)s.Hq * s.nchunks * sa::kWin * 8);
+  c->off[3] = o; o += align256((size_t)s.Hq * sa::kWin * 8);
+  c->off[4] = o; o += align256((size_t)s.Hq * (s.N / 32) * 4);
+  c->off[5] = o; o += align256((size_t)s.Hq * (s.N / 32) * 4);
+  c->ws_bytes = o;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *sa_version(void) { return "sa-prefill-gfx950 0.1"; }
+
+sa_status sa_default_budgets(sa_config *cfg, double keep) {
+  if (!cfg || !(keep > 0.0) || keep > 1.0) return SA_ERR_INVALID_ARG;
+  if (cfg->block <= 0 || cfg->seq_len <= 0 || cfg->seq_len % cfg->block) return SA_ERR_INVALID_ARG;
+  const long long N = cfg->seq_len, nb = N / cfg->block;
+  const long long causal = nb * (nb + 1) / 2;
+  long long T = (long long)std::floor(keep * (double)causal + 0.5);
+  if (T < nb) T = nb;
+  const int sink = 1;
+  int L = 1;
+  for (long long cand = 1; cand <= nb; ++cand)
+    if (cand * nb - cand * (cand - 1) / 2 + (nb - cand) * sink <= T) L = (int)cand;
+  long long ks = (long long)std::floor(keep * (double)N / 128.0 + 0.5);
+  long long kv = (long long)std::floor(keep * (double)N / 256.0 + 0.5);
+  if (ks < 1) ks = 1;
+  if (kv < 1) kv = 1;
+  kv *= 64;
+  if (kv > N) kv = N;
+  if (ks > N) ks = N;
+  cfg->sink_blocks = sink;
+  cfg->local_blocks = L;
+  cfg->k_vertical = (int32_t)kv;
+  cfg->k_slash = (int32_t)ks;
+  cfg->k_blocks = (int32_t)T;
+  return SA_OK;
+}
+
+sa_status sa_create(const sa_config *cfg, sa_ctx **out) {
+  if (!cfg || !out) return SA_ERR_INVALID_ARG;
+  *out = nullptr;
+  if (cfg->head_dim != sa::kHeadDim) return SA_ERR_UNSUPPORTED;
+  if (cfg->block != 64 && cfg->block != 128) return SA_ERR_UNSUPPORTED;
+  if (cfg->seq_len <= 0 || cfg->seq_len % cfg->block) return SA_ERR_UNSUPPORTED;
+  if (cfg->seq_len > sa::kMaxSeq) return SA_ERR_UNSUPPORTED;
+  if (cfg->last_q < 1 || cfg->last_q > sa::kWin || cfg->last_q > cfg->seq_len) return SA_ERR_UNSUPPORTED;
+  if (cfg->n_q_heads <= 0 || cfg->n_kv_heads <= 0 || cfg->n_q_heads % cfg->n_kv_heads ||
+      cfg->n_q_heads > sa::kMaxHeads)
+    return SA_ERR_INVALID_ARG;
+  const int nb = cfg->seq_len / cfg->block;
+  if (cfg->sink_blocks < 0 || cfg->local_blocks < 1 || cfg->local_blocks > nb) return SA_ERR_INVALID_ARG;
+  if (cfg->k_vertical < 1 || cfg->k_slash < 1 || cfg->k_blocks < nb) return SA_ERR_INVALID_ARG;
+  if (cfg->probe_v < 0 || cfg->probe_s < 0 || cfg->lift_num < 0 || cfg->lift_den < 0) return SA_ERR_INVALID_ARG;
+  if (cfg->softmax_scale < 0.f) return SA_ERR_INVALID_ARG;
+
+  sa_ctx *c = new (std::nothrow) sa_ctx();
+  if (!c) return SA_ERR_INVALID_ARG;
+  c->cfg = *cfg;
+  sa::Shape &s = c->sh;
+  s.Hq = cfg->n_q_heads; s.Hkv = cfg->n_kv_heads; s.g = s.Hq / s.Hkv;
+  s.N = cfg->seq_len; s.b = cfg->block; s.nb = nb; s.w = cfg->last_q;
+  s.k_v = cfg->k_vertical; s.k_s = cfg->k_slash; s.k_b = cfg->k_blocks;
+  s.sink = cfg->sink_blocks; s.local = cfg->local_blocks;
+  s.probe_v = cfg->probe_v ? cfg->probe_v : 4;
+  s.probe_s = cfg->probe_s ? cfg->probe_s : 4;
+  s.lift_num = cfg->lift_num ? cfg->lift_num : 4;
+  s.lift_den = cfg->lift_den ? cfg->lift_den : 1;
+  const long long tri = triangular_count(nb, s.sink, s.local);
+  const long long cap = tri > s.k_b ? tri : s.k_b;
+  if (cap > 0x7FFFFFFFll) { delete c; return SA_ERR_UNSUPPORTED; }
+  s.cap_b = (int)cap;
+  s.nchunks = (s.N + sa::kChunk - 1) / sa::kChunk;
+  s.q_rs = cfg->q_row_stride ? cfg->q_row_stride : sa::kHeadDim;
+  s.q_hs = cfg->q_head_stride ? cfg->q_head_stride : (int64_t)s.N * s.q_rs;
+  s.kv_rs = cfg->kv_row_stride ? cfg->kv_row_stride : sa::kHeadDim;
+  s.kv_hs = cfg->kv_head_stride ? cfg->kv_head_stride : (int64_t)s.N * s.kv_rs;
+  if (s.q_rs % 8 || s.kv_rs % 8 || s.q_hs % 8 || s.kv_hs % 8 || s.q_rs < sa::kHeadDim ||
+      s.kv_rs < sa::kHeadDim) {
+    delete c;
+    return SA_ERR_UNSUPPORTED;
+  }
+  s.scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)sa::kHeadDim);
+  c->have_ws = false;
+  c->err[0] = 0;
+  carve(c);
+  *out = c;
+  return SA_OK;
+}
+
+void sa_destroy(sa_ctx *ctx) { delete ctx; }
+
+sa_status sa_scores_bytes(const sa_ctx *c, size_t out[3]) {
+  if (!c || !out) return SA_ERR_INVALID_ARG;
+  out[0] = out[1] = (size_t)c->sh.Hq * c->sh.N * 4;
+  out[2] = (size_t)c->sh.Hq * c->sh.nb * c->sh.nb * 4;
+  return SA_OK;
+}
+
+sa_status sa_index_bytes(const sa_ctx *c, size_t out[7]) {
+  if (!c || !out) return SA_ERR_INVALID_ARG;
+  const sa::Shape &s = c->sh;
+  out[0] = (size_t)s.Hq * 4;
+  out[1] = (size_t)s.Hq * 4;
+  out[2] = (size_t)s.Hq * s.k_v * 4;
+  out[3] = (size_t)s.Hq * 4;
+  out[4] = (size_t)s.Hq * s.k_s * 4;
+  out[5] = (size_t)s.Hq * (s.nb + 1) * 4;
+  out[6] = (size_t)s.Hq * s.cap_b * 4;
+  return SA_OK;
+}
+
+sa_status sa_workspace_bytes(const sa_ctx *c, size_t *bytes) {
+  if (!c || !bytes) return SA_ERR_INVALID_ARG;
+  *bytes = c->ws_bytes;
+  return SA_OK;
+}
+
+sa_status sa_set_workspace(sa_ctx *c, void *dev, size_t bytes) {
+  if (!c) return SA_ERR_INVALID_ARG;
+  if (!dev || ((uintptr_t)dev & 255)) return fail(c, SA_ERR_INVALID_ARG, "workspace must be a 256-byte aligned device pointer");
+  if (bytes < c->ws_bytes) return fail(c, SA_ERR_BUFFER_TOO_SMALL, "workspace smaller than sa_workspace_bytes");
+  char *p = (char *)dev;
+  c->ws.qblk = (float *)(p + c->off[0]);
+  c->ws.kblk = (float *)(p + c->off[1]);
+  c->ws.part = (float2 *)(p + c->off[2]);
+  c->ws.stats = (float2 *)(p + c->off[3]);
+  c->ws.offbits = (uint32_t *)(p + c->off[4]);
+  c->ws.colbits = (uint32_t *)(p + c->off[5]);
+  c->have_ws = true;
+  return SA_OK;
+}
+
+static sa_status hip_result(sa_ctx *c, hipError_t e) {
+  if (e == hipSuccess) return SA_OK;
+  snprintf(c->err, sizeof(c->err), "HIP: %s", hipGetErrorString(e));
+  return SA_ERR_HIP;
+}
+
+sa_status sa_estimate_patterns(sa_ctx *c, const void *Q, const void *K, sa_scores out, void *stream) {
+  if (!c) return SA_ERR_INVALID_ARG;
+  if (!Q || !K || !out.v || !out.s || !out.blk) return fail(c, SA_ERR_INVALID_ARG, "null pointer");
+  if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)out.blk) & 15) return fail(c, SA_ERR_INVALID_ARG, "Q, K, blk must be 16-byte aligned");
+  if (!c->have_ws) return fail(c, SA_ERR_INVALID_ARG, "no workspace attached");
+  return hip_result(c, sa::launch_estimate(c->sh, c->ws, (const uint16_t *)Q, (const uint16_t *)K, out,
+                                           (hipStream_t)stream));
+}
+
+sa_status sa_build_index(sa_ctx *c, sa_scores in, const int32_t *override_host, sa_index out,
+                         void *stream) {
+  if (!c) return SA_ERR_INVALID_ARG;
+  if (!in.v || !in.s || !in.blk || !out.pattern || !out.n_cols || !out.cols || !out.n_offs ||
+      !out.offs || !out.rowptr || !out.blkcols)
+    return fail(c, SA_ERR_INVALID_ARG, "null pointer");
+  sa::Override ov;
+  for (int h = 0; h < sa::kMaxHeads; ++h) ov.pat[h] = -1;
+  if (override_host)
+    for (int h = 0; h < c->sh.Hq; ++h) {
+      const int32_t p = override_host[h];
+      if (p < -1 || p > 2) return fail(c, SA_ERR_INVALID_ARG, "pattern override out of range");
+      ov.pat[h] = (int8_t)p;
+    }
+  return hip_result(c, sa::launch_build_index(c->sh, c->ws, in, ov, out, (hipStream_t)stream));
+}
+
+sa_status sa_sparse_prefill(sa_ctx *c, const void *Q, const void *K, const void *V, sa_index idx,
+                            void *O, void *stream) {
+  if (!c) return SA_ERR_INVALID_ARG;
+  if (!Q || !K || !V || !O || !idx.n_cols || !idx.cols || !idx.n_offs || !idx.offs || !idx.rowptr ||
+      !idx.blkcols)
+    return fail(c, SA_ERR_INVALID_ARG, "null pointer");
+  if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15)
+    return fail(c, SA_ERR_INVALID_ARG, "Q, K, V, O must be 16-byte aligned");
+  if (!c->have_ws) return fail(c, SA_ERR_INVALID_ARG, "no workspace attached");
+  return hip_result(c, sa::launch_sparse_prefill(c->sh, c->ws, (const uint16_t *)Q, (const uint16_t *)K,
+                                                 (const uint16_t *)V, idx, (uint16_t *)O,
+                                                 (hipStream_t)stream));
+}
+
+const char *sa_last_error(const sa_ctx *c) { return c ? c->err : "null context"; }
+
+}  // extern "C"

@@ -1,0 +1,389 @@
+// Sparse causal prefill attention for gfx950 (Alg. 2 / Alg. 3 "Compute Sparse
+// Attention": softmax over the kept keys only, then the product with V).
+//
+// One workgroup = 128 query rows of one head (4 waves x 32 rows).  The key axis
+// is walked in tiles of 64 keys:
+//   * range tiles  - aligned key tiles that hold a kept block of the CSR or a
+//                    piece of a selected diagonal;
+//   * gather tiles - 64 selected key columns, rows fetched one by one (each a
+//                    256-byte coalesced read).
+// A key is counted once: selected columns are masked out of range tiles and
+// served by the gather tiles only.  Per tile each wave computes
+// S^T = K Q^T (keys x queries) with v_mfma_f32_32x32x16_bf16, so that one lane
+// owns one query: the online softmax needs a single cross-lane exchange, and
+// the probabilities are already laid out as the B operand of O^T += V^T P^T.
+#include "sa_internal.h"
+
+namespace sa {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int BQ = 128;           // query rows per workgroup
+constexpr int BK = 64;            // keys per tile
+constexpr int KS = 136;           // LDS row stride in 16-bit elements (272 B: conflict-free b128 reads)
+constexpr int NWORDS = kMaxSeq / BK / 32;
+
+struct AttnArgs {
+  const uint16_t *Q, *K, *V;
+  uint16_t *O;
+  const int32_t *n_cols, *cols, *n_offs, *offs, *rowptr, *blkcols;
+  const uint32_t *offbits, *colbits;
+  int Hq, Hkv, g, N, b, nb, nT, k_v, k_s, cap_b;
+  int64_t q_hs, q_rs, kv_hs, kv_rs;
+  float c;  // softmax scale * log2(e)
+};
+
+// Membership bitmaps of the selected columns and diagonal offsets, one block per head.
+__global__ void index_bitmaps_kernel(const int32_t *n_cols, const int32_t *cols,
+                                     const int32_t *n_offs, const int32_t *offs, int k_v, int k_s,
+                                     int N, uint32_t *colbits, uint32_t *offbits) {
+  const int h = blockIdx.x, nw = N / 32;
+  for (int i = threadIdx.x; i < nw; i += blockDim.x) {
+    colbits[(size_t)h * nw + i] = 0u;
+    offbits[(size_t)h * nw + i] = 0u;
+  }
+  __syncthreads();
+  const int nc = min(max(n_cols[h], 0), k_v), no = min(max(n_offs[h], 0), k_s);
+  for (int i = threadIdx.x; i < nc; i += blockDim.x) {
+    const int c = cols[(size_t)h * k_v + i];
+    if (c >= 0 && c < N) atomicOr(&colbits[(size_t)h * nw + (c >> 5)], 1u << (c & 31));
+  }
+  for (int i = threadIdx.x; i < no; i += blockDim.x) {
+    const int o = offs[(size_t)h * k_s + i];
+    if (o >= 0 && o < N) atomicOr(&offbits[(size_t)h * nw + (o >> 5)], 1u << (o & 31));
+  }
+}
+
+__device__ inline uint32_t bits_word(const uint32_t *bm, int nw, int wi) {
+  return (wi >= 0 && wi < nw) ? bm[wi] : 0u;
+}
+
+// 64 bits of a bitmap starting at bit position `pos` (may be negative or run past the end).
+__device__ inline uint64_t bits_window64(const uint32_t *bm, int nw, int pos) {
+  const int wi = pos >> 5, sh = pos & 31;  // arithmetic shift: floor for negatives
+  const uint64_t lo = (uint64_t)bits_word(bm, nw, wi) | ((uint64_t)bits_word(bm, nw, wi + 1) << 32);
+  const uint64_t hi = (uint64_t)bits_word(bm, nw, wi + 2);
+  return sh ? ((lo >> sh) | (hi << (64 - sh))) : lo;
+}
+
+__global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
+  __shared__ __attribute__((aligned(16))) uint16_t Ks[BK * KS];
+  __shared__ __attribute__((aligned(16))) uint16_t Vs[BK * KS];
+  __shared__ uint32_t need[NWORDS], kept0[NWORDS], kept1[NWORDS];
+  __shared__ uint16_t tlist[kMaxSeq / BK];
+  __shared__ int s_ntiles;
+
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int q = lane & 31, gg = lane >> 5;
+
+  // work item: KV heads rotate fastest so that one XCD keeps one KV head in its L2;
+  // the longest (last) row blocks start first.
+  const int id = blockIdx.x;
+  const int kvh = id % p.Hkv;
+  const int rest = id / p.Hkv;
+  const int h = kvh * p.g + rest % p.g;
+  const int t128 = p.nT - 1 - rest / p.g;
+  const int i0 = t128 * BQ;
+  const int r0 = i0 + 32 * wv;
+  const int iq = r0 + q;  // this lane's query row
+  const int N = p.N;
+  const int ilast = min(i0 + BQ, N) - 1;
+
+  // ---- tile list of this row block -------------------------------------------------------
+  const int nwords = ((ilast / BK + 1) + 31) / 32;
+  for (int i = tid; i < nwords; i += 256) { need[i] = 0u; kept0[i] = 0u; kept1[i] = 0u; }
+  __syncthreads();
+  {
+    const int32_t *rp = p.rowptr + (size_t)h * (p.nb + 1);
+    const int32_t *bc = p.blkcols + (size_t)h * p.cap_b;
+    if (p.b == BQ) {
+      const int e0 = max(rp[t128], 0), e1 = min(rp[t128 + 1], p.cap_b);
+      for (int e = e0 + tid; e < e1; e += 256) {
+        const int C = bc[e];
+        if (C >= 0 && C <= t128) {
+          const int kt = 2 * C;  // two key tiles per 128-key block: adjacent bits of one word
+          atomicOr(&need[kt >> 5], 3u << (kt & 31));
+          atomicOr(&kept0[kt >> 5], 3u << (kt & 31));
+          atomicOr(&kept1[kt >> 5], 3u << (kt & 31));
+        }
+      }
+    } else {  // block 64: this workgroup covers row blocks 2*t128 (waves 0,1) and 2*t128+1 (waves 2,3)
+      for (int half = 0; half < 2; ++half) {
+        const int R = 2 * t128 + half;
+        if (R >= p.nb) break;
+        uint32_t *kept = half ? kept1 : kept0;
+        const int e0 = max(rp[R], 0), e1 = min(rp[R + 1], p.cap_b);
+        for (int e = e0 + tid; e < e1; e += 256) {
+          const int C = bc[e];
+          if (C >= 0 && C <= R) {
+            atomicOr(&need[C >> 5], 1u << (C & 31));
+            atomicOr(&kept[C >> 5], 1u << (C & 31));
+          }
+        }
+      }
+    }
+    const int no = min(max(p.n_offs[h], 0), p.k_s);
+    for (int e = tid; e < no; e += 256) {
+      const int o = p.offs[(size_t)h * p.k_s + e];
+      if (o < 0) continue;
+      const int hi = ilast - o;
+      if (hi < 0) continue;
+      const int lo = max(i0 - o, 0);
+      for (int kt = lo / BK; kt <= hi / BK; ++kt) atomicOr(&need[kt >> 5], 1u << (kt & 31));
+    }
+  }
+  __syncthreads();
+  if (wv == 0) {  // ordered compaction of the set bits into tlist
+    int base = 0;
+    for (int w0 = 0; w0 < nwords; w0 += 64) {
+      const uint32_t word = (w0 + lane < nwords) ? need[w0 + lane] : 0u;
+      const int cnt = __popc(word);
+      int incl = cnt;
+      for (int d = 1; d < 64; d <<= 1) {
+        const int o = __shfl_up(incl, d);
+        if (lane >= d) incl += o;
+      }
+      int pos = base + incl - cnt;
+      uint32_t wbits = word;
+      while (wbits) {
+        const int bit = __ffs(wbits) - 1;
+        wbits &= wbits - 1;
+        tlist[pos++] = (uint16_t)((w0 + lane) * 32 + bit);
+      }
+      base += __shfl(incl, 63);
+    }
+    if (lane == 0) s_ntiles = base;
+  }
+  __syncthreads();
+  const int ntr = s_ntiles;
+
+  // gathered columns: how many selected columns are visible to this row block / this query
+  const int nc = min(max(p.n_cols[h], 0), p.k_v);
+  const int32_t *colp = p.cols + (size_t)h * p.k_v;
+  int cle;  // number of selected columns <= iq (ascending list: binary search)
+  {
+    int lo = 0, hi = nc;
+    const int key = min(iq, N - 1);
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (colp[mid] <= key) lo = mid + 1; else hi = mid;
+    }
+    cle = lo;
+  }
+  // the last valid lane of the workgroup sees the most columns
+  int cmax = cle;
+  for (int d = 32; d >= 1; d >>= 1) cmax = max(cmax, __shfl_xor(cmax, d));
+  __shared__ int s_cmax[4];
+  if (lane == 0) s_cmax[wv] = cmax;
+  __syncthreads();
+  const int call = max(max(s_cmax[0], s_cmax[1]), max(s_cmax[2], s_cmax[3]));
+  const int ng = (call + BK - 1) / BK;
+  const int ntot = ntr + ng;
+  const bool has_cols = nc > 0;
+  const bool has_offs = p.n_offs[h] > 0;
+
+  // ---- operands ------------------------------------------------------------------------------
+  const uint16_t *Kh = p.K + (size_t)kvh * p.kv_hs;
+  const uint16_t *Vh = p.V + (size_t)kvh * p.kv_hs;
+  const uint32_t *offbm = p.offbits + (size_t)h * (N / 32);
+  const uint32_t *colbm = p.colbits + (size_t)h * (N / 32);
+
+  bf16x8 qf[8];  // Q^T fragments: B operand, lane = query, 8 consecutive d per k-step half
+  {
+    const uint16_t *qrow = p.Q + (size_t)h * p.q_hs + (size_t)min(iq, N - 1) * p.q_rs;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qf[ks] = *(const bf16x8 *)(qrow + 16 * ks + 8 * gg);
+  }
+
+  f32x16 oacc[4];
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+
+  // staging registers of the global -> LDS pipeline: this thread moves rows lrow+16n, 16-byte column lcc
+  uint4 kreg[4], vreg[4];
+  const int lrow = tid >> 4, lcc = tid & 15;
+
+  auto issue_loads = [&](int t) {
+#pragma unroll
+    for (int n = 0; n < 4; ++n) {
+      const int row = lrow + 16 * n;
+      int src;
+      if (t < ntr) {
+        src = (int)tlist[t] * BK + row;
+      } else {
+        const int ci = (t - ntr) * BK + row;
+        src = ci < nc ? colp[ci] : 0;
+        src = min(max(src, 0), N - 1);
+      }
+      kreg[n] = *(const uint4 *)(Kh + (size_t)src * p.kv_rs + lcc * 8);
+      vreg[n] = *(const uint4 *)(Vh + (size_t)src * p.kv_rs + lcc * 8);
+    }
+  };
+
+  if (ntot > 0) issue_loads(0);
+
+  for (int t = 0; t < ntot; ++t) {
+    __syncthreads();
+#pragma unroll
+    for (int n = 0; n < 4; ++n) {
+      const int row = lrow + 16 * n;
+      *(uint4 *)&Ks[row * KS + lcc * 8] = kreg[n];
+      *(uint4 *)&Vs[row * KS + lcc * 8] = vreg[n];
+    }
+    __syncthreads();
+    if (t + 1 < ntot) issue_loads(t + 1);
+
+    // ---- what this wave keeps of the tile: a 64-bit mask per lane over the key slots ---------
+    // slot c (0..59 used) stands for key_local = c + 4*gg; see the accumulator layout below.
+    bool active, needmask;
+    uint64_t km;
+    if (t < ntr) {
+      const int kt = tlist[t];
+      const int j0 = kt * BK;
+      const bool bk = (((wv < 2 ? kept0 : kept1)[kt >> 5] >> (kt & 31)) & 1u) != 0;
+      const bool beyond = j0 > min(r0 + 31, N - 1);
+      uint64_t dwin_lo = 0, dwin_hi = 0;  // 95-bit window of kept offsets, bit k <-> offset r0-j0-63+k
+      if (has_offs && !bk && !beyond) {
+        const int s0 = r0 - j0 - 63;
+        dwin_lo = bits_window64(offbm, N / 32, s0);
+        dwin_hi = bits_window64(offbm, N / 32, s0 + 64) & 0x7FFFFFFFull;
+      }
+      active = !beyond && (bk || (dwin_lo | dwin_hi) != 0);
+      const uint64_t vm = has_cols ? ((uint64_t)colbm[2 * kt] | ((uint64_t)colbm[2 * kt + 1] << 32)) : 0ull;
+      needmask = !(bk && vm == 0 && j0 + 63 <= r0);
+      km = ~0ull;
+      if (active && needmask) {
+        const int lim = iq - j0 - 4 * gg;  // causal: slot c kept iff c <= lim
+        const uint64_t cm = lim < 0 ? 0ull : (lim >= 63 ? ~0ull : ((2ull << lim) - 1ull));
+        km = cm & ~(vm >> (4 * gg));
+        if (!bk) {
+          // offset of (query q, slot c) sits at window bit q - 4gg + 63 - c = B - c, B in [59,94]:
+          // shift so that it lands at bit 59 - c, then reverse to bit c.
+          const int sh = q - 4 * gg + 4;  // B - 59, in [0,35]
+          const uint64_t y = sh ? ((dwin_lo >> sh) | (dwin_hi << (64 - sh))) : dwin_lo;
+          km &= __brevll(y) >> 4;
+        }
+      }
+    } else {
+      const int gi = t - ntr;
+      const int cnt = cle - gi * BK;  // visible columns of this tile for this query
+      const int lim = cnt - 1 - 4 * gg;
+      km = lim < 0 ? 0ull : (lim >= 63 ? ~0ull : ((2ull << lim) - 1ull));
+      needmask = true;
+      active = __any(cnt > 0);
+    }
+    if (!active) continue;
+
+    // ---- S^T = K Q^T : lane = query (q), accumulator r of half hf <-> key 32hf + 8(r/4) + 4gg + r%4
+    f32x16 sacc[2];
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sacc[hf][r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        const bf16x8 a = *(const bf16x8 *)&Ks[(32 * hf + q) * KS + 16 * ks + 8 * gg];
+        sacc[hf] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], sacc[hf], 0, 0, 0);
+      }
+    }
+    if (needmask) {
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int c = 32 * hf + 8 * (r / 4) + (r % 4);
+          if (!((km >> c) & 1ull)) sacc[hf][r] = -INFINITY;
+        }
+    }
+    // ---- online softmax (log2 domain) -----------------------------------------------------------
+    float tmax = -INFINITY;
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, sacc[hf][r]);
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+    const float m_new = fmaxf(m_run, tmax * p.c);
+    const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
+    m_run = m_new;
+    float psum = 0.f;
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[hf][r], p.c, -m_safe));
+        sacc[hf][r] = pe;
+        psum += pe;
+      }
+    l_run = l_run * alpha + psum;
+    if (__any(alpha != 1.f)) {
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+    }
+    // ---- O^T += V^T P^T : k-slot (gg,e) of step (hf,u) <-> key 32hf + 16u + 8(e/4) + 4gg + e%4 ----
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        bf16x8 pb;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pb[e] = (__bf16)sacc[hf][8 * u + e];
+#pragma unroll
+        for (int db = 0; db < 4; ++db) {
+          union { bf16x8 v; uint16_t s[8]; } a;
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            a.s[e] = Vs[(32 * hf + 16 * u + 8 * (e / 4) + 4 * gg + (e % 4)) * KS + 32 * db + q];
+          oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, pb, oacc[db], 0, 0, 0);
+        }
+      }
+  }
+
+  // ---- epilogue: O[iq][32db + 8(r/4) + 4gg + r%4] = oacc / l -------------------------------------
+  const float ltot = l_run + __shfl_xor(l_run, 32);
+  const float inv = ltot > 0.f ? 1.f / ltot : 0.f;
+  if (iq < N) {
+    uint16_t *orow = p.O + (size_t)h * p.q_hs + (size_t)iq * p.q_rs;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int rb = 0; rb < 4; ++rb) {
+        union { __bf16 b[4]; uint2 u; } o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o.b[e] = (__bf16)(oacc[db][4 * rb + e] * inv);
+        *(uint2 *)(orow + 32 * db + 8 * rb + 4 * gg) = o.u;
+      }
+  }
+}
+
+}  // namespace
+
+hipError_t launch_sparse_prefill(const Shape &sh, const Workspace &ws, const uint16_t *Q,
+                                 const uint16_t *K, const uint16_t *V, sa_index idx, uint16_t *O,
+                                 hipStream_t st) {
+  index_bitmaps_kernel<<<sh.Hq, 256, 0, st>>>(idx.n_cols, idx.cols, idx.n_offs, idx.offs, sh.k_v,
+                                              sh.k_s, sh.N, ws.colbits, ws.offbits);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  AttnArgs a;
+  a.Q = Q; a.K = K; a.V = V; a.O = O;
+  a.n_cols = idx.n_cols; a.cols = idx.cols; a.n_offs = idx.n_offs; a.offs = idx.offs;
+  a.rowptr = idx.rowptr; a.blkcols = idx.blkcols;
+  a.offbits = ws.offbits; a.colbits = ws.colbits;
+  a.Hq = sh.Hq; a.Hkv = sh.Hkv; a.g = sh.g; a.N = sh.N; a.b = sh.b; a.nb = sh.nb;
+  a.nT = (sh.N + BQ - 1) / BQ;
+  a.k_v = sh.k_v; a.k_s = sh.k_s; a.cap_b = sh.cap_b;
+  a.q_hs = sh.q_hs; a.q_rs = sh.q_rs; a.kv_hs = sh.kv_hs; a.kv_rs = sh.kv_rs;
+  a.c = sh.scale * 1.4426950408889634f;
+  sparse_prefill_kernel<<<a.nT * sh.Hq, 256, 0, st>>>(a);
+  return hipGetLastError();
+}
+
+}  // namespace sa

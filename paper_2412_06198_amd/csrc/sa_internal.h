@@ -1,0 +1,43 @@
+// Internal declarations shared by the host API and the kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "sa.h"
+
+namespace sa {
+
+constexpr int kHeadDim = 128;
+constexpr int kMaxHeads = 128;
+constexpr int kWin = 64;          // rows of the last-query window the estimator tiles for
+constexpr int kChunk = 256;       // keys per estimator workgroup
+constexpr int kMaxSeq = 262144;   // key-tile bitmaps of the attention kernel cover this many keys
+
+struct Override { int8_t pat[kMaxHeads]; };
+
+// Everything the kernels need, resolved from sa_config at sa_create time.
+struct Shape {
+  int Hq, Hkv, g, N, b, nb, w;
+  int k_v, k_s, k_b, cap_b, sink, local;
+  int probe_v, probe_s, lift_num, lift_den;
+  int nchunks;                    // ceil(N / kChunk)
+  int64_t q_hs, q_rs, kv_hs, kv_rs;
+  float scale;
+};
+
+struct Workspace {
+  float *qblk, *kblk;             // [Hq][nb][128], [Hkv][nb][128] block means
+  float2 *part;                   // [Hq][nchunks][64] partial (max, sum) of the window rows
+  float2 *stats;                  // [Hq][64] (max * scale*log2e, 1/sum)
+  uint32_t *offbits, *colbits;    // [Hq][N/32] membership bitmaps of offs / cols
+};
+
+hipError_t launch_estimate(const Shape &sh, const Workspace &ws, const uint16_t *Q,
+                           const uint16_t *K, sa_scores out, hipStream_t st);
+hipError_t launch_build_index(const Shape &sh, const Workspace &ws, sa_scores in,
+                              const Override &ov, sa_index out, hipStream_t st);
+hipError_t launch_sparse_prefill(const Shape &sh, const Workspace &ws, const uint16_t *Q,
+                                 const uint16_t *K, const uint16_t *V, sa_index idx, uint16_t *O,
+                                 hipStream_t st);
+
+}  // namespace sa

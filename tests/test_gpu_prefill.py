@@ -1,0 +1,90 @@
+"""GPU parity of sa_sparse_prefill against the fp64 oracle (through the C ABI).
+
+Tolerance: bf16 inputs, fp32 accumulation -> max-abs 2e-2 and mean-abs 2e-3 against fp64."""
+import numpy as np
+import pytest
+import torch
+
+from harness import gen
+from oracle import oracle as orc
+from gpu_util import (check_attention, dev_bf16, host_f64, make_session, upload_index)
+
+pytestmark = pytest.mark.gpu
+T, IS, BC = 0, 1, 2
+
+
+def _run(ses, Q, K, V):
+    Qd, Kd, Vd = dev_bf16(Q), dev_bf16(K), dev_bf16(V)
+    O = torch.empty_like(Qd)
+    ses.prefill(Qd, Kd, Vd, O)
+    torch.cuda.synchronize()
+    return host_f64(O)
+
+
+@pytest.mark.parametrize("Hq,Hkv,N,b", [(4, 2, 512, 64), (2, 1, 448, 64), (4, 4, 768, 128),
+                                        (2, 2, 64, 64), (1, 1, 128, 128)])
+def test_all_blocks_index_equals_dense(Hq, Hkv, N, b):
+    print(f"case all-blocks Hq={Hq} Hkv={Hkv} N={N} b={b}", flush=True)
+    nb = N // b
+    Q, K, V = gen.random_qkv(Hq, Hkv, N, 128, seed=N + b)
+    bud = orc.Budgets(1, 1, 1, 1, nb * (nb + 1) // 2)
+    z = np.zeros((Hq, N), np.float32)
+    ix = orc.build_index(z, z, np.ones((Hq, nb, nb), np.float32), N, b, min(64, N), bud,
+                         override=[BC] * Hq)
+    ses = make_session(Hq, Hkv, N, b, min(64, N), bud)
+    upload_index(ses, ix)
+    O = _run(ses, Q, K, V)
+    ref, _ = orc.dense_rows(Q, K, V)
+    check_attention(O, ref, "dense")
+
+
+@pytest.mark.parametrize("N,b,seed", [(1024, 64, 1), (1024, 128, 2), (832, 64, 3)])
+def test_mixed_index_matches_oracle(N, b, seed):
+    print(f"case mixed N={N} b={b} seed={seed}", flush=True)
+    Hq, Hkv, w = 6, 2, 64
+    Q, K, V = gen.random_qkv(Hq, Hkv, N, 128, seed=seed)
+    v, s, blk = (x.astype(np.float32) for x in orc.estimate(Q, K, b, w))
+    nb = N // b
+    bud = orc.Budgets(1, 2, 70, 5, nb + 3 * nb)
+    ix = orc.build_index(v, s, blk, N, b, w, bud, override=[T, IS, BC, IS, BC, T])
+    ses = make_session(Hq, Hkv, N, b, w, bud)
+    upload_index(ses, ix)
+    O = _run(ses, Q, K, V)
+    ref, ws, _ = orc.masked_rows(Q, K, V, b, ix)
+    check_attention(O, ref, "mixed")
+
+
+def test_union_of_all_three_parts_in_one_head():
+    # an index no single pattern produces: blocks + columns + diagonals together
+    print("case union", flush=True)
+    Hq, Hkv, N, b, w = 2, 1, 640, 64, 64
+    Q, K, V = gen.random_qkv(Hq, Hkv, N, 128, seed=12)
+    v, s, blk = (x.astype(np.float32) for x in orc.estimate(Q, K, b, w))
+    nb = N // b
+    bud = orc.Budgets(1, 2, 33, 4, nb + 12)
+    a = orc.build_index(v, s, blk, N, b, w, bud, override=[IS, IS])
+    c = orc.build_index(v, s, blk, N, b, w, bud, override=[BC, BC])
+    mix = orc.Index(a.pattern, a.n_cols, a.cols, a.n_offs, a.offs, c.rowptr, c.blkcols)
+    ses = make_session(Hq, Hkv, N, b, w, bud)
+    upload_index(ses, mix)
+    O = _run(ses, Q, K, V)
+    ref, _, _ = orc.masked_rows(Q, K, V, b, mix)
+    check_attention(O, ref, "union")
+
+
+def test_planted_cfg1_shape_full_rows():
+    # the tiny benchmark configuration in full: every row of every head against the oracle
+    print("case cfg1", flush=True)
+    wl = gen.WORKLOADS["cfg1"]
+    data = gen.generate(wl)
+    N, b, w = wl.seq_len, wl.block, wl.last_q
+    v, s, blk = (x.astype(np.float32) for x in orc.estimate(data["Q"], data["K"], b, w))
+    bud = orc.default_budgets(N, b, wl.keep)
+    ix = orc.build_index(v, s, blk, N, b, w, bud, override=[IS, T, BC, IS])
+    ses = make_session(wl.n_q_heads, wl.n_kv_heads, N, b, w, bud)
+    upload_index(ses, ix)
+    O = _run(ses, data["Q"], data["K"], data["V"])
+    ref, ws, _ = orc.masked_rows(data["Q"], data["K"], data["V"], b, ix)
+    check_attention(O, ref, "cfg1")
+    O2 = _run(ses, data["Q"], data["K"], data["V"])
+    assert (O == O2).all()                      # deterministic run to run
