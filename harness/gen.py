@@ -23,6 +23,8 @@ and K themselves, beta = 3, a = c = sqrt(beta*sqrt(d))):
 """
 from __future__ import annotations
 
+import os
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass, field
 
 import numpy as np
@@ -170,15 +172,21 @@ def generate(wl: Workload, seed: int | None = None, plants: list[HeadPlant] | No
     g = Hq // Hkv
     if plants is None:
         plants = draw_plants(wl, seed)
-    rng = np.random.Generator(np.random.Philox(key=[seed, 0]))
     crng = np.random.Generator(np.random.Philox(key=[seed, 0x51ED270B]))
 
     a = c = float(np.sqrt(BETA * np.sqrt(d)))
     diag_gain = np.float32(BETA * np.sqrt(d) / PLANT_LO)
 
-    K0 = rng.standard_normal((Hkv, N, d), dtype=np.float32)
+    # every head draws from its own Philox stream, so heads can be generated in parallel
+    def base(stream):
+        r = np.random.Generator(np.random.Philox(key=[seed, stream]))
+        return r.standard_normal((N, d), dtype=np.float32)
+
+    workers = max(1, min(16, os.cpu_count() or 1))
+    with ThreadPoolExecutor(max_workers=workers) as ex:
+        K0 = np.stack(list(ex.map(lambda kv: base(1000 + kv), range(Hkv))))
+        V = np.stack(list(ex.map(lambda kv: base(2000 + kv), range(Hkv))))
     K0[:, :, PLANT_LO:] = 0.0
-    V = rng.standard_normal((Hkv, N, d), dtype=np.float32)
     K = K0.copy()
     Qb = np.empty((Hq, N, d), dtype=np.uint16)
 
@@ -211,9 +219,10 @@ def generate(wl: Workload, seed: int | None = None, plants: list[HeadPlant] | No
         qside.append(ops)
 
     # ... then each query head
-    for h, p in enumerate(plants):
+    def make_q(h):
+        p = plants[h]
         kv = h // g
-        q = rng.standard_normal((N, d), dtype=np.float32)
+        q = base(3000 + h)
         q[:, PLANT_LO:] = 0.0
         ops = qside[h]
         if ops["ch"] is not None:
@@ -232,6 +241,9 @@ def generate(wl: Workload, seed: int | None = None, plants: list[HeadPlant] | No
             hb = p.hot_block
             q[R * hb:(R + 1) * hb, CODE_LO:] += np.float32(c) * u
         Qb[h] = f32_to_bf16_bits(q)
+
+    with ThreadPoolExecutor(max_workers=workers) as ex:
+        list(ex.map(make_q, range(Hq)))
 
     return {
         "Q": Qb,

@@ -123,8 +123,15 @@ sa_status sa_build_index(sa_ctx *ctx, sa_scores in, const int32_t *pattern_overr
 sa_status sa_sparse_prefill(sa_ctx *ctx, const void *Q, const void *K, const void *V,
                             sa_index idx, void *O, void *hip_stream);
 
-/* Average duration in milliseconds of the kernels launched by the last compute
- * call is not tracked here; time with HIP events on the stream you pass. */
+/* Same computation and output as sa_sparse_prefill, plus work accounting for
+ * the FLOP figures of a benchmark: adds to counters_dev[0] the number of
+ * (wave, key tile) pairs the kernel multiplied (32 queries x 64 keys each) and
+ * to counters_dev[1] the number of kept (query, key) pairs, |M| of the sparse
+ * softmax of Alg. 2 / Alg. 3.  counters_dev: DEVICE uint64[2], zeroed by the
+ * caller.  Slower than sa_sparse_prefill (atomics); never time it. */
+sa_status sa_sparse_prefill_counted(sa_ctx *ctx, const void *Q, const void *K, const void *V,
+                                    sa_index idx, void *O, uint64_t *counters_dev,
+                                    void *hip_stream);
 
 const char *sa_last_error(const sa_ctx *ctx);
 

@@ -68,6 +68,10 @@ class Index:
                 self.blkcols]
 
 
+def num_threads() -> int:
+    return int(lib().oracle_num_threads())
+
+
 def default_scale(d):
     return 1.0 / float(np.sqrt(float(d)))
 

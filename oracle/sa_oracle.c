@@ -30,6 +30,7 @@
  * fp64 attention, closed forms, brute force, invariants).  None is unpinned.
  */
 #include <math.h>
+#include <omp.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -50,6 +51,9 @@ static double dot_bf16(const uint16_t *a, const uint16_t *b, int d) {
   for (int t = 0; t < d; ++t) acc += bf16_to_f64(a[t]) * bf16_to_f64(b[t]);
   return acc;
 }
+
+/* OpenMP threads the loops below will use. */
+int oracle_num_threads(void) { return omp_get_max_threads(); }
 
 /* ------------------------------------------------------------------ dense */
 

@@ -2,5 +2,5 @@
 from .binding import (  # noqa: F401
     SaConfig, SaError, SaIndex, SaScores, Session, library, sa_build_index, sa_create,
     sa_default_budgets, sa_destroy, sa_estimate_patterns, sa_index_bytes, sa_last_error,
-    sa_scores_bytes, sa_set_workspace, sa_sparse_prefill, sa_version, sa_workspace_bytes,
+    sa_scores_bytes, sa_set_workspace, sa_sparse_prefill, sa_sparse_prefill_counted, sa_version, sa_workspace_bytes,
 )

@@ -70,9 +70,10 @@ def library():
         lib.sa_estimate_patterns.argtypes = [vp, vp, vp, SaScores, vp]
         lib.sa_build_index.argtypes = [vp, SaScores, C.POINTER(C.c_int32), SaIndex, vp]
         lib.sa_sparse_prefill.argtypes = [vp, vp, vp, vp, SaIndex, vp, vp]
+        lib.sa_sparse_prefill_counted.argtypes = [vp, vp, vp, vp, SaIndex, vp, vp, vp]
         for f in ("sa_default_budgets", "sa_create", "sa_scores_bytes", "sa_index_bytes",
                   "sa_workspace_bytes", "sa_set_workspace", "sa_estimate_patterns",
-                  "sa_build_index", "sa_sparse_prefill"):
+                  "sa_build_index", "sa_sparse_prefill", "sa_sparse_prefill_counted"):
             getattr(lib, f).restype = st
         _lib = lib
     return _lib
@@ -151,6 +152,11 @@ def sa_sparse_prefill(ctx, Q, K, V, index: SaIndex, O, stream=None):
     _check(library().sa_sparse_prefill(ctx, _ptr(Q), _ptr(K), _ptr(V), index, _ptr(O), stream), ctx)
 
 
+def sa_sparse_prefill_counted(ctx, Q, K, V, index: SaIndex, O, counters, stream=None):
+    _check(library().sa_sparse_prefill_counted(ctx, _ptr(Q), _ptr(K), _ptr(V), index, _ptr(O),
+                                               _ptr(counters), stream), ctx)
+
+
 class Session:
     """Owns a context plus the torch-allocated score / index / workspace buffers of one shape."""
 
@@ -212,6 +218,13 @@ class Session:
 
     def prefill(self, Q, K, V, O):
         sa_sparse_prefill(self.ctx, Q, K, V, self.index(), O, self.stream())
+
+    def prefill_counted(self, Q, K, V, O):
+        """Returns (active wave-tiles, kept query-key pairs) of one prefill call."""
+        cnt = self.torch.zeros(2, dtype=self.torch.int64, device=self.device)
+        sa_sparse_prefill_counted(self.ctx, Q, K, V, self.index(), O, cnt, self.stream())
+        self.torch.cuda.synchronize(self.device)
+        return [int(x) for x in cnt.cpu()]
 
     def close(self):
         if self.ctx is not None:

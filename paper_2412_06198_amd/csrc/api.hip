@@ -205,8 +205,8 @@ sa_status sa_build_index(sa_ctx *c, sa_scores in, const int32_t *override_host, 
   return hip_result(c, sa::launch_build_index(c->sh, c->ws, in, ov, out, (hipStream_t)stream));
 }
 
-sa_status sa_sparse_prefill(sa_ctx *c, const void *Q, const void *K, const void *V, sa_index idx,
-                            void *O, void *stream) {
+static sa_status prefill_common(sa_ctx *c, const void *Q, const void *K, const void *V, sa_index idx,
+                                void *O, uint64_t *counters, void *stream) {
   if (!c) return SA_ERR_INVALID_ARG;
   if (!Q || !K || !V || !O || !idx.n_cols || !idx.cols || !idx.n_offs || !idx.offs || !idx.rowptr ||
       !idx.blkcols)
@@ -216,7 +216,19 @@ sa_status sa_sparse_prefill(sa_ctx *c, const void *Q, const void *K, const void 
   if (!c->have_ws) return fail(c, SA_ERR_INVALID_ARG, "no workspace attached");
   return hip_result(c, sa::launch_sparse_prefill(c->sh, c->ws, (const uint16_t *)Q, (const uint16_t *)K,
                                                  (const uint16_t *)V, idx, (uint16_t *)O,
-                                                 (hipStream_t)stream));
+                                                 (unsigned long long *)counters, (hipStream_t)stream));
+}
+
+sa_status sa_sparse_prefill(sa_ctx *c, const void *Q, const void *K, const void *V, sa_index idx,
+                            void *O, void *stream) {
+  return prefill_common(c, Q, K, V, idx, O, nullptr, stream);
+}
+
+sa_status sa_sparse_prefill_counted(sa_ctx *c, const void *Q, const void *K, const void *V,
+                                    sa_index idx, void *O, uint64_t *counters_dev, void *stream) {
+  if (c && (!counters_dev || ((uintptr_t)counters_dev & 7)))
+    return fail(c, SA_ERR_INVALID_ARG, "counters must be an 8-byte aligned device pointer");
+  return prefill_common(c, Q, K, V, idx, O, counters_dev, stream);
 }
 
 const char *sa_last_error(const sa_ctx *c) { return c ? c->err : "null context"; }

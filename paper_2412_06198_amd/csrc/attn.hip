@@ -33,6 +33,7 @@ struct AttnArgs {
   int Hq, Hkv, g, N, b, nb, nT, k_v, k_s, cap_b;
   int64_t q_hs, q_rs, kv_hs, kv_rs;
   float c;  // softmax scale * log2(e)
+  unsigned long long *counters;  // instrumentation only: {active wave-tiles, kept (query,key) pairs}
 };
 
 // Membership bitmaps of the selected columns and diagonal offsets, one block per head.
@@ -68,6 +69,7 @@ __device__ inline uint64_t bits_window64(const uint32_t *bm, int nw, int pos) {
   return sh ? ((lo >> sh) | (hi << (64 - sh))) : lo;
 }
 
+template <bool STATS>
 __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
   __shared__ __attribute__((aligned(16))) uint16_t Ks[BK * KS];
   __shared__ __attribute__((aligned(16))) uint16_t Vs[BK * KS];
@@ -278,6 +280,15 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
       active = __any(cnt > 0);
     }
     if (!active) continue;
+    if constexpr (STATS) {
+      // slots this lane owns: c = 32hf + 8(r/4) + r%4
+      unsigned long long kept = iq < N ? (unsigned long long)__popcll(km & 0x0F0F0F0F0F0F0F0Full) : 0ull;
+      for (int d = 32; d >= 1; d >>= 1) kept += __shfl_xor(kept, d);
+      if (lane == 0) {
+        atomicAdd(&p.counters[0], 1ull);
+        atomicAdd(&p.counters[1], kept);
+      }
+    }
 
     // ---- S^T = K Q^T : lane = query (q), accumulator r of half hf <-> key 32hf + 8(r/4) + 4gg + r%4
     f32x16 sacc[2];
@@ -367,7 +378,7 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
 
 hipError_t launch_sparse_prefill(const Shape &sh, const Workspace &ws, const uint16_t *Q,
                                  const uint16_t *K, const uint16_t *V, sa_index idx, uint16_t *O,
-                                 hipStream_t st) {
+                                 unsigned long long *counters, hipStream_t st) {
   index_bitmaps_kernel<<<sh.Hq, 256, 0, st>>>(idx.n_cols, idx.cols, idx.n_offs, idx.offs, sh.k_v,
                                               sh.k_s, sh.N, ws.colbits, ws.offbits);
   hipError_t e = hipGetLastError();
@@ -382,7 +393,11 @@ hipError_t launch_sparse_prefill(const Shape &sh, const Workspace &ws, const uin
   a.k_v = sh.k_v; a.k_s = sh.k_s; a.cap_b = sh.cap_b;
   a.q_hs = sh.q_hs; a.q_rs = sh.q_rs; a.kv_hs = sh.kv_hs; a.kv_rs = sh.kv_rs;
   a.c = sh.scale * 1.4426950408889634f;
-  sparse_prefill_kernel<<<a.nT * sh.Hq, 256, 0, st>>>(a);
+  a.counters = counters;
+  if (counters)
+    sparse_prefill_kernel<true><<<a.nT * sh.Hq, 256, 0, st>>>(a);
+  else
+    sparse_prefill_kernel<false><<<a.nT * sh.Hq, 256, 0, st>>>(a);
   return hipGetLastError();
 }
 

@@ -38,6 +38,6 @@ hipError_t launch_build_index(const Shape &sh, const Workspace &ws, sa_scores in
                               const Override &ov, sa_index out, hipStream_t st);
 hipError_t launch_sparse_prefill(const Shape &sh, const Workspace &ws, const uint16_t *Q,
                                  const uint16_t *K, const uint16_t *V, sa_index idx, uint16_t *O,
-                                 hipStream_t st);
+                                 unsigned long long *counters, hipStream_t st);
 
 }  // namespace sa

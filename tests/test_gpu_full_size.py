@@ -1,0 +1,101 @@
+"""Whole path at the benchmark's sizes, in the launch configuration bench.py times:
+scores by tolerance, index bit-exact on the GPU's own scores, attention on sampled rows."""
+import numpy as np
+import pytest
+import torch
+
+from harness import gen
+from oracle import oracle as orc
+from gpu_util import (assert_index_equal, check_attention, dev_bf16, download_index,
+                      download_scores, host_f64)
+import paper_2412_06198_amd as sa
+
+pytestmark = pytest.mark.gpu
+
+
+def _whole_path(name, n_rows, margin_check=True):
+    print(f"case full-size {name}", flush=True)
+    wl = gen.WORKLOADS[name]
+    data = gen.generate(wl)
+    N, b, w, Hq = wl.seq_len, wl.block, wl.last_q, wl.n_q_heads
+    ses = sa.Session(Hq, wl.n_kv_heads, N, b, w, keep=wl.keep)
+    Q, K, V = dev_bf16(data["Q"]), dev_bf16(data["K"]), dev_bf16(data["V"])
+    O = torch.empty_like(Q)
+    ses.estimate(Q, K)
+    ses.build_index(None)
+    ses.prefill(Q, K, V, O)
+    v, s, blk = download_scores(ses)
+    got = download_index(ses)
+    print("  gpu done; oracle estimate", flush=True)
+    # 1. scores
+    rv, rs, rblk = orc.estimate(data["Q"], data["K"], b, w)
+    for nm, g_, r_ in (("v", v, rv), ("s", s, rs), ("blk", blk, rblk)):
+        bad = np.abs(g_ - r_) > 1e-3 * np.abs(r_) + 1e-6 * w
+        assert not bad.any(), (nm, int(bad.sum()))
+    # 2. selection: bit-exact on the GPU's own fp32 scores
+    bud = orc.default_budgets(N, b, wl.keep)
+    want = orc.build_index(v, s, blk, N, b, w, bud)
+    assert_index_equal(got, want)
+    # 3. end to end: heads whose pattern decision and top-k boundaries are not near-ties in
+    #    fp64 must give the same index from the oracle's own scores
+    e2e = orc.build_index(rv.astype(np.float32), rs.astype(np.float32), rblk.astype(np.float32),
+                          N, b, w, bud)
+    same = [h for h in range(Hq) if all(a[h].tobytes() == c[h].tobytes()
+                                        for a, c in zip(got.arrays(), e2e.arrays()))]
+    print(f"  end-to-end identical heads: {len(same)}/{Hq}; patterns {got.pattern.tolist()}", flush=True)
+    assert (got.pattern == e2e.pattern).all()
+    for h in range(Hq):
+        if h in same:
+            continue
+        # differing heads may only differ by candidates whose fp64 scores tie within 1e-3
+        for arr_g, arr_o, sc in ((got.cols[h], e2e.cols[h], rv[h]), (got.offs[h], e2e.offs[h], rs[h])):
+            a, c = set(arr_g[arr_g >= 0].tolist()), set(arr_o[arr_o >= 0].tolist())
+            if a != c:
+                lo = min(sc[list(a | c)])
+                for j in a ^ c:
+                    assert abs(sc[j] - lo) <= 2e-3 * lo, (h, j)
+    # 4. attention on sampled rows, oracle evaluated on the GPU's index
+    rng = np.random.Generator(np.random.Philox(key=[wl.seed, 5]))
+    rows = np.sort(np.concatenate([rng.choice(N, n_rows - 3, replace=False), [0, N // 2 + 1, N - 1]])).astype(np.int32)
+    rows = np.unique(rows)
+    ref, ws, _ = orc.masked_rows(data["Q"], data["K"], data["V"], b, got, rows=rows)
+    assert np.abs(ws - 1).max() < 1e-9
+    check_attention(host_f64(O[:, torch.from_numpy(rows.astype(np.int64)).cuda()]), ref, name)
+    return ses, (Q, K, V, O), got
+
+
+def test_cfg2_16k():
+    _whole_path("cfg2", 96)
+
+
+def test_cfg3_32k():
+    _whole_path("cfg3", 96)
+
+
+def test_cfg4_64k():
+    _whole_path("cfg4", 64)
+
+
+def test_cfg5_128k_one_layer():
+    _whole_path("cfg5", 48)
+
+
+def test_counters_match_oracle_mask_count():
+    print("case counters", flush=True)
+    Hq, Hkv, N, b, w = 4, 2, 1024, 64, 64
+    Q, K, V = gen.random_qkv(Hq, Hkv, N, 128, seed=3)
+    bud = orc.Budgets(1, 2, 40, 3, N // b + 20)
+    ses = sa.Session(Hq, Hkv, N, b, w, sink_blocks=1, local_blocks=2, k_vertical=40, k_slash=3,
+                     k_blocks=N // b + 20)
+    Qd, Kd, Vd = dev_bf16(Q), dev_bf16(K), dev_bf16(V)
+    O = torch.empty_like(Qd)
+    ses.estimate(Qd, Kd)
+    ses.build_index([0, 1, 2, 1])
+    tiles, kept = ses.prefill_counted(Qd, Kd, Vd, O)
+    ix = download_index(ses)
+    assert kept == sum(orc.mask_count(N, b, h, ix) for h in range(Hq))
+    assert tiles * 32 * 64 >= kept
+    O2 = torch.empty_like(Qd)
+    ses.prefill(Qd, Kd, Vd, O2)
+    torch.cuda.synchronize()
+    assert torch.equal(O, O2)
