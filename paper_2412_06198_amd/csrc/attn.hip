@@ -19,10 +19,13 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int BQ = 128;           // query rows per workgroup
 constexpr int BK = 64;            // keys per tile
 constexpr int KS = 136;           // LDS row stride in 16-bit elements (272 B: conflict-free b128 reads)
+constexpr int KSV = 160;          // V tile row stride (320 B): the transposing reads below hit 64 distinct banks
 constexpr int NWORDS = kMaxSeq / BK / 32;
 
 struct AttnArgs {
@@ -72,7 +75,7 @@ __device__ inline uint64_t bits_window64(const uint32_t *bm, int nw, int pos) {
 template <bool STATS>
 __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
   __shared__ __attribute__((aligned(16))) uint16_t Ks[BK * KS];
-  __shared__ __attribute__((aligned(16))) uint16_t Vs[BK * KS];
+  __shared__ __attribute__((aligned(16))) uint16_t Vs[BK * KSV];
   __shared__ uint32_t need[NWORDS], kept0[NWORDS], kept1[NWORDS];
   __shared__ uint16_t tlist[kMaxSeq / BK];
   __shared__ int s_ntiles;
@@ -207,38 +210,49 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
   float m_run = -INFINITY, l_run = 0.f;
 
   // staging registers of the global -> LDS pipeline: this thread moves rows lrow+16n, 16-byte column lcc
-  uint4 kreg[4], vreg[4];
+  uint4 k0, k1, k2, k3, v0, v1, v2, v3;
   const int lrow = tid >> 4, lcc = tid & 15;
+  const uint16_t *Kc = Kh + lcc * 8, *Vc = Vh + lcc * 8;
 
-  auto issue_loads = [&](int t) {
-#pragma unroll
-    for (int n = 0; n < 4; ++n) {
-      const int row = lrow + 16 * n;
-      int src;
-      if (t < ntr) {
-        src = (int)tlist[t] * BK + row;
-      } else {
-        const int ci = (t - ntr) * BK + row;
-        src = ci < nc ? colp[ci] : 0;
-        src = min(max(src, 0), N - 1);
-      }
-      kreg[n] = *(const uint4 *)(Kh + (size_t)src * p.kv_rs + lcc * 8);
-      vreg[n] = *(const uint4 *)(Vh + (size_t)src * p.kv_rs + lcc * 8);
+  auto src_row = [&](int t, int row) -> size_t {
+    int src;
+    if (t < ntr) {
+      src = (int)tlist[t] * BK + row;
+    } else {
+      const int ci = (t - ntr) * BK + row;
+      src = ci < nc ? colp[ci] : 0;
+      src = min(max(src, 0), N - 1);
     }
+    return (size_t)src * p.kv_rs;
   };
+#define SA_ISSUE_LOADS(t)                                                            \
+  {                                                                                  \
+    const size_t o0 = src_row(t, lrow), o1 = src_row(t, lrow + 16),                  \
+                 o2 = src_row(t, lrow + 32), o3 = src_row(t, lrow + 48);             \
+    k0 = *(const uint4 *)(Kc + o0); k1 = *(const uint4 *)(Kc + o1);                  \
+    k2 = *(const uint4 *)(Kc + o2); k3 = *(const uint4 *)(Kc + o3);                  \
+    v0 = *(const uint4 *)(Vc + o0); v1 = *(const uint4 *)(Vc + o1);                  \
+    v2 = *(const uint4 *)(Vc + o2); v3 = *(const uint4 *)(Vc + o3);                  \
+  }
 
-  if (ntot > 0) issue_loads(0);
+  // this lane's source address of the transposing V reads (see the P V step)
+  typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+  const uint16_t *vtr = &Vs[(4 * gg + ((lane & 15) >> 2)) * KSV + 16 * ((lane >> 4) & 1) + 4 * (lane & 3)];
+
+  if (ntot > 0) SA_ISSUE_LOADS(0);
 
   for (int t = 0; t < ntot; ++t) {
     __syncthreads();
-#pragma unroll
-    for (int n = 0; n < 4; ++n) {
-      const int row = lrow + 16 * n;
-      *(uint4 *)&Ks[row * KS + lcc * 8] = kreg[n];
-      *(uint4 *)&Vs[row * KS + lcc * 8] = vreg[n];
-    }
+    *(uint4 *)&Ks[(lrow + 0) * KS + lcc * 8] = k0;
+    *(uint4 *)&Ks[(lrow + 16) * KS + lcc * 8] = k1;
+    *(uint4 *)&Ks[(lrow + 32) * KS + lcc * 8] = k2;
+    *(uint4 *)&Ks[(lrow + 48) * KS + lcc * 8] = k3;
+    *(uint4 *)&Vs[(lrow + 0) * KSV + lcc * 8] = v0;
+    *(uint4 *)&Vs[(lrow + 16) * KSV + lcc * 8] = v1;
+    *(uint4 *)&Vs[(lrow + 32) * KSV + lcc * 8] = v2;
+    *(uint4 *)&Vs[(lrow + 48) * KSV + lcc * 8] = v3;
     __syncthreads();
-    if (t + 1 < ntot) issue_loads(t + 1);
+    if (t + 1 < ntot) SA_ISSUE_LOADS(t + 1);
 
     // ---- what this wave keeps of the tile: a 64-bit mask per lane over the key slots ---------
     // slot c (0..59 used) stands for key_local = c + 4*gg; see the accumulator layout below.
@@ -319,26 +333,33 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
       for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, sacc[hf][r]);
     tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
     const float m_new = fmaxf(m_run, tmax * p.c);
-    const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
-    m_run = m_new;
-    float psum = 0.f;
-#pragma unroll
-    for (int hf = 0; hf < 2; ++hf)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[hf][r], p.c, -m_safe));
-        sacc[hf][r] = pe;
-        psum += pe;
-      }
-    l_run = l_run * alpha + psum;
-    if (__any(alpha != 1.f)) {
+    // The reference maximum moves only when some row's maximum grew by more than 2^8: until
+    // then probabilities may exceed 1 (by at most 256x), which fp32 sums and bf16 P hold easily,
+    // and the 64 accumulator registers are not rescaled.
+    if (__any(m_new - m_run > 8.f)) {
+      const float alpha = __builtin_amdgcn_exp2f(m_run - ((m_new == -INFINITY) ? 0.f : m_new));
+      m_run = m_new;
+      l_run *= alpha;
 #pragma unroll
       for (int db = 0; db < 4; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
     }
+    const float m_ref = (m_run == -INFINITY) ? 0.f : m_run;
+    float psum = 0.f;
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[hf][r], p.c, -m_ref));
+        sacc[hf][r] = pe;
+        psum += pe;
+      }
+    l_run += psum;
     // ---- O^T += V^T P^T : k-slot (gg,e) of step (hf,u) <-> key 32hf + 16u + 8(e/4) + 4gg + e%4 ----
+    // V sits row-major [key][d] in LDS; ds_read_b64_tr_b16 hands each lane four consecutive keys
+    // of ONE d column: within 16 lanes, source lane r supplies the 8-byte piece (key r/4,
+    // d 4(r%4)..+3) and receives (keys 0..3, d r).  Two such reads form the A operand.
 #pragma unroll
     for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
@@ -348,11 +369,12 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
         for (int e = 0; e < 8; ++e) pb[e] = (__bf16)sacc[hf][8 * u + e];
 #pragma unroll
         for (int db = 0; db < 4; ++db) {
-          union { bf16x8 v; uint16_t s[8]; } a;
-#pragma unroll
-          for (int e = 0; e < 8; ++e)
-            a.s[e] = Vs[(32 * hf + 16 * u + 8 * (e / 4) + 4 * gg + (e % 4)) * KS + 32 * db + q];
-          oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, pb, oacc[db], 0, 0, 0);
+          const uint16_t *src = vtr + (32 * hf + 16 * u) * KSV + 32 * db;
+          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)src);
+          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(src + 8 * KSV));
+          const s16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pb,
+                                                             oacc[db], 0, 0, 0);
         }
       }
   }
@@ -373,6 +395,8 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
       }
   }
 }
+
+#undef SA_ISSUE_LOADS
 
 }  // namespace
 
