@@ -13,7 +13,7 @@ struct sa_ctx {
   sa::Workspace ws;
   bool have_ws;
   size_t ws_bytes;
-  size_t off[6];
+  size_t off[8];
   char err[256];
 };
 
@@ -44,6 +44,9 @@ void carve(sa_ctx *c) {
   c->off[3] = o; o += align256((size_t)s.Hq * sa::kWin * 8);
   c->off[4] = o; o += align256((size_t)s.Hq * (s.N / 32) * 4);
   c->off[5] = o; o += align256((size_t)s.Hq * (s.N / 32) * 4);
+  const size_t kvg = (size_t)s.Hq * ((s.k_v + 63) / 64 * 64) * sa::kHeadDim * 2;
+  c->off[6] = o; o += align256(kvg);
+  c->off[7] = o; o += align256(kvg);
   c->ws_bytes = o;
 }
 
@@ -169,6 +172,8 @@ sa_status sa_set_workspace(sa_ctx *c, void *dev, size_t bytes) {
   c->ws.stats = (float2 *)(p + c->off[3]);
   c->ws.offbits = (uint32_t *)(p + c->off[4]);
   c->ws.colbits = (uint32_t *)(p + c->off[5]);
+  c->ws.kg = (uint16_t *)(p + c->off[6]);
+  c->ws.vg = (uint16_t *)(p + c->off[7]);
   c->have_ws = true;
   return SA_OK;
 }

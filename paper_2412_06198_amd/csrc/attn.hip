@@ -24,8 +24,6 @@ typedef short s16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int BQ = 128;           // query rows per workgroup
 constexpr int BK = 64;            // keys per tile
-constexpr int KS = 136;           // LDS row stride in 16-bit elements (272 B: conflict-free b128 reads)
-constexpr int KSV = 160;          // V tile row stride (320 B): the transposing reads below hit 64 distinct banks
 constexpr int NWORDS = kMaxSeq / BK / 32;
 
 struct AttnArgs {
@@ -33,6 +31,8 @@ struct AttnArgs {
   uint16_t *O;
   const int32_t *n_cols, *cols, *n_offs, *offs, *rowptr, *blkcols;
   const uint32_t *offbits, *colbits;
+  uint16_t *Kg, *Vg;  // [Hq][kvg_rows][128] selected key columns, gathered once per call
+  int kvg_rows;
   int Hq, Hkv, g, N, b, nb, nT, k_v, k_s, cap_b;
   int64_t q_hs, q_rs, kv_hs, kv_rs;
   float c;  // softmax scale * log2(e)
@@ -60,27 +60,55 @@ __global__ void index_bitmaps_kernel(const int32_t *n_cols, const int32_t *cols,
   }
 }
 
-__device__ inline uint32_t bits_word(const uint32_t *bm, int nw, int wi) {
+__device__ inline uint32_t bits_word(const uint32_t *__restrict__ bm, int nw, int wi) {
   return (wi >= 0 && wi < nw) ? bm[wi] : 0u;
 }
 
 // 64 bits of a bitmap starting at bit position `pos` (may be negative or run past the end).
-__device__ inline uint64_t bits_window64(const uint32_t *bm, int nw, int pos) {
+__device__ inline uint64_t bits_window64(const uint32_t *__restrict__ bm, int nw, int pos) {
   const int wi = pos >> 5, sh = pos & 31;  // arithmetic shift: floor for negatives
   const uint64_t lo = (uint64_t)bits_word(bm, nw, wi) | ((uint64_t)bits_word(bm, nw, wi + 1) << 32);
   const uint64_t hi = (uint64_t)bits_word(bm, nw, wi + 2);
   return sh ? ((lo >> sh) | (hi << (64 - sh))) : lo;
 }
 
+// The selected key columns of every head, copied once into contiguous [k][d] buffers so that
+// the attention kernel reads gather tiles like any other tile.  grid (ceil(k_v/64), Hq).
+__global__ __launch_bounds__(256) void gather_columns_kernel(AttnArgs p) {
+  const int h = blockIdx.y, g = blockIdx.x, tid = threadIdx.x;
+  const int nc = min(max(p.n_cols[h], 0), p.k_v);
+  if (g * BK >= nc) return;
+  const int kvh = h / p.g;
+  const int lrow = tid >> 4, lcc = tid & 15;
+#pragma unroll
+  for (int n = 0; n < 4; ++n) {
+    const int ci = g * BK + lrow + 16 * n;
+    int src = ci < nc ? p.cols[(size_t)h * p.k_v + ci] : 0;
+    src = min(max(src, 0), p.N - 1);
+    const size_t so = (size_t)kvh * p.kv_hs + (size_t)src * p.kv_rs + lcc * 8;
+    const size_t dofs = ((size_t)h * p.kvg_rows + ci) * kHeadDim + lcc * 8;
+    *(uint4 *)(p.Kg + dofs) = *(const uint4 *)(p.K + so);
+    *(uint4 *)(p.Vg + dofs) = *(const uint4 *)(p.V + so);
+  }
+}
+
+// LDS tiles are 64 rows x 256 B with the 16-byte chunks of a row XOR-swizzled (no padding):
+//   K: chunk c of row r sits at chunk c ^ (r & 15)      -> b128 reads of 16 rows hit 64 banks
+//   V: chunk c of row r sits at chunk c ^ ((r & 3) << 2) -> the transposing b64 reads do
+__device__ inline int kswz(int row, int chunk) { return row * 128 + ((chunk ^ (row & 15)) << 3); }
+__device__ inline int vswz(int row, int chunk) { return row * 128 + ((chunk ^ ((row & 3) << 2)) << 3); }
+
 template <bool STATS>
 __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
-  __shared__ __attribute__((aligned(16))) uint16_t Ks[BK * KS];
-  __shared__ __attribute__((aligned(16))) uint16_t Vs[BK * KSV];
+  __shared__ __attribute__((aligned(16))) uint16_t Ks[2][BK * 128];
+  __shared__ __attribute__((aligned(16))) uint16_t Vs[2][BK * 128];
   __shared__ uint32_t need[NWORDS], kept0[NWORDS], kept1[NWORDS];
   __shared__ uint16_t tlist[kMaxSeq / BK];
   __shared__ int s_ntiles;
+  __shared__ int s_cmax[4];
 
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform for the compiler too
   const int q = lane & 31, gg = lane >> 5;
 
   // work item: KV heads rotate fastest so that one XCD keeps one KV head in its L2;
@@ -161,14 +189,12 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
     }
     if (lane == 0) s_ntiles = base;
   }
-  __syncthreads();
-  const int ntr = s_ntiles;
 
-  // gathered columns: how many selected columns are visible to this row block / this query
+  // gathered columns: how many selected columns are visible to this query (ascending list)
   const int nc = min(max(p.n_cols[h], 0), p.k_v);
-  const int32_t *colp = p.cols + (size_t)h * p.k_v;
-  int cle;  // number of selected columns <= iq (ascending list: binary search)
+  int cle;
   {
+    const int32_t *colp = p.cols + (size_t)h * p.k_v;
     int lo = 0, hi = nc;
     const int key = min(iq, N - 1);
     while (lo < hi) {
@@ -177,23 +203,25 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
     }
     cle = lo;
   }
-  // the last valid lane of the workgroup sees the most columns
   int cmax = cle;
   for (int d = 32; d >= 1; d >>= 1) cmax = max(cmax, __shfl_xor(cmax, d));
-  __shared__ int s_cmax[4];
   if (lane == 0) s_cmax[wv] = cmax;
   __syncthreads();
-  const int call = max(max(s_cmax[0], s_cmax[1]), max(s_cmax[2], s_cmax[3]));
+  const int ntr = __builtin_amdgcn_readfirstlane(s_ntiles);
+  const int cwave = __builtin_amdgcn_readfirstlane(cmax);
+  const int call = __builtin_amdgcn_readfirstlane(max(max(s_cmax[0], s_cmax[1]), max(s_cmax[2], s_cmax[3])));
   const int ng = (call + BK - 1) / BK;
   const int ntot = ntr + ng;
   const bool has_cols = nc > 0;
   const bool has_offs = p.n_offs[h] > 0;
 
   // ---- operands ------------------------------------------------------------------------------
-  const uint16_t *Kh = p.K + (size_t)kvh * p.kv_hs;
-  const uint16_t *Vh = p.V + (size_t)kvh * p.kv_hs;
-  const uint32_t *offbm = p.offbits + (size_t)h * (N / 32);
-  const uint32_t *colbm = p.colbits + (size_t)h * (N / 32);
+  const uint16_t *__restrict__ Kh = p.K + (size_t)kvh * p.kv_hs;
+  const uint16_t *__restrict__ Vh = p.V + (size_t)kvh * p.kv_hs;
+  const uint16_t *__restrict__ Kgh = p.Kg + (size_t)h * p.kvg_rows * kHeadDim;
+  const uint16_t *__restrict__ Vgh = p.Vg + (size_t)h * p.kvg_rows * kHeadDim;
+  const uint32_t *__restrict__ offbm = p.offbits + (size_t)h * (N / 32);
+  const uint32_t *__restrict__ colbm = p.colbits + (size_t)h * (N / 32);
 
   bf16x8 qf[8];  // Q^T fragments: B operand, lane = query, 8 consecutive d per k-step half
   {
@@ -209,57 +237,73 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
     for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
 
-  // staging registers of the global -> LDS pipeline: this thread moves rows lrow+16n, 16-byte column lcc
+  // ---- global -> register -> LDS pipeline ------------------------------------------------------
+  // this thread moves rows lrow+16n (n=0..3), 16-byte chunk lcc, of the K and the V tile
   uint4 k0, k1, k2, k3, v0, v1, v2, v3;
   const int lrow = tid >> 4, lcc = tid & 15;
-  const uint16_t *Kc = Kh + lcc * 8, *Vc = Vh + lcc * 8;
+  const int kst = kswz(lrow, lcc), vst = vswz(lrow, lcc);  // rows +16n keep (row & 15), (row & 3)
 
-  auto src_row = [&](int t, int row) -> size_t {
-    int src;
-    if (t < ntr) {
-      src = (int)tlist[t] * BK + row;
-    } else {
-      const int ci = (t - ntr) * BK + row;
-      src = ci < nc ? colp[ci] : 0;
-      src = min(max(src, 0), N - 1);
-    }
-    return (size_t)src * p.kv_rs;
-  };
-#define SA_ISSUE_LOADS(t)                                                            \
-  {                                                                                  \
-    const size_t o0 = src_row(t, lrow), o1 = src_row(t, lrow + 16),                  \
-                 o2 = src_row(t, lrow + 32), o3 = src_row(t, lrow + 48);             \
-    k0 = *(const uint4 *)(Kc + o0); k1 = *(const uint4 *)(Kc + o1);                  \
-    k2 = *(const uint4 *)(Kc + o2); k3 = *(const uint4 *)(Kc + o3);                  \
-    v0 = *(const uint4 *)(Vc + o0); v1 = *(const uint4 *)(Vc + o1);                  \
-    v2 = *(const uint4 *)(Vc + o2); v3 = *(const uint4 *)(Vc + o3);                  \
+#define SA_ISSUE_LOADS(t)                                                                    \
+  {                                                                                          \
+    const uint16_t *kb, *vb;                                                                 \
+    size_t rs;                                                                               \
+    if ((t) < ntr) {                                                                         \
+      const int j0_ = __builtin_amdgcn_readfirstlane((int)tlist[t]) * BK;                    \
+      kb = Kh + (size_t)j0_ * p.kv_rs; vb = Vh + (size_t)j0_ * p.kv_rs; rs = (size_t)p.kv_rs; \
+    } else {                                                                                 \
+      const size_t g0_ = (size_t)((t) - ntr) * BK * kHeadDim;                                \
+      kb = Kgh + g0_; vb = Vgh + g0_; rs = kHeadDim;                                         \
+    }                                                                                        \
+    const size_t o_ = (size_t)lrow * rs + lcc * 8;                                           \
+    k0 = *(const uint4 *)(kb + o_); k1 = *(const uint4 *)(kb + o_ + 16 * rs);                \
+    k2 = *(const uint4 *)(kb + o_ + 32 * rs); k3 = *(const uint4 *)(kb + o_ + 48 * rs);      \
+    v0 = *(const uint4 *)(vb + o_); v1 = *(const uint4 *)(vb + o_ + 16 * rs);                \
+    v2 = *(const uint4 *)(vb + o_ + 32 * rs); v3 = *(const uint4 *)(vb + o_ + 48 * rs);      \
+  }
+#define SA_STORE_TILE(buf)                                                                   \
+  {                                                                                          \
+    *(uint4 *)&Ks[buf][kst] = k0; *(uint4 *)&Ks[buf][kst + 16 * 128] = k1;                   \
+    *(uint4 *)&Ks[buf][kst + 32 * 128] = k2; *(uint4 *)&Ks[buf][kst + 48 * 128] = k3;        \
+    *(uint4 *)&Vs[buf][vst] = v0; *(uint4 *)&Vs[buf][vst + 16 * 128] = v1;                   \
+    *(uint4 *)&Vs[buf][vst + 32 * 128] = v2; *(uint4 *)&Vs[buf][vst + 48 * 128] = v3;        \
   }
 
-  // this lane's source address of the transposing V reads (see the P V step)
+  // per-lane LDS offsets (16-bit elements) of the operand reads
+  //   K (A of S^T): row 32hf + q, chunk 2ks + gg  ->  b128
+  int koff[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) koff[ks] = kswz(q, 2 * ks + gg);  // + 32hf*128 : (row & 15) unchanged
+  //   V (A of O^T, transposing read): within 16 lanes, source lane r supplies the 8-byte piece
+  //   (key r/4, d 4(r%4)..+3) and receives (keys 0..3, d r); lanes 16..31 take d 16..31.
   typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-  const uint16_t *vtr = &Vs[(4 * gg + ((lane & 15) >> 2)) * KSV + 16 * ((lane >> 4) & 1) + 4 * (lane & 3)];
+  int voff[4];
+  {
+    const int r = lane & 15, grp = (lane >> 4) & 1;
+    const int row = 4 * gg + (r >> 2);  // + 32hf + 16u + 8x : multiples of 4 keep (row & 3)
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+      voff[db] = vswz(row, 4 * db + 2 * grp + ((r & 3) >> 1)) + 4 * (r & 1);
+  }
 
-  if (ntot > 0) SA_ISSUE_LOADS(0);
+  if (ntot > 0) {
+    SA_ISSUE_LOADS(0);
+    SA_STORE_TILE(0);
+    if (ntot > 1) SA_ISSUE_LOADS(1);
+  }
 
   for (int t = 0; t < ntot; ++t) {
+    const int cur = t & 1;
+    // tile t is complete in LDS[cur]; every wave has finished reading LDS[cur^1] (tile t-1)
     __syncthreads();
-    *(uint4 *)&Ks[(lrow + 0) * KS + lcc * 8] = k0;
-    *(uint4 *)&Ks[(lrow + 16) * KS + lcc * 8] = k1;
-    *(uint4 *)&Ks[(lrow + 32) * KS + lcc * 8] = k2;
-    *(uint4 *)&Ks[(lrow + 48) * KS + lcc * 8] = k3;
-    *(uint4 *)&Vs[(lrow + 0) * KSV + lcc * 8] = v0;
-    *(uint4 *)&Vs[(lrow + 16) * KSV + lcc * 8] = v1;
-    *(uint4 *)&Vs[(lrow + 32) * KSV + lcc * 8] = v2;
-    *(uint4 *)&Vs[(lrow + 48) * KSV + lcc * 8] = v3;
-    __syncthreads();
-    if (t + 1 < ntot) SA_ISSUE_LOADS(t + 1);
+    if (t + 1 < ntot) SA_STORE_TILE(cur ^ 1);
+    if (t + 2 < ntot) SA_ISSUE_LOADS(t + 2);
 
     // ---- what this wave keeps of the tile: a 64-bit mask per lane over the key slots ---------
     // slot c (0..59 used) stands for key_local = c + 4*gg; see the accumulator layout below.
     bool active, needmask;
     uint64_t km;
     if (t < ntr) {
-      const int kt = tlist[t];
+      const int kt = __builtin_amdgcn_readfirstlane((int)tlist[t]);
       const int j0 = kt * BK;
       const bool bk = (((wv < 2 ? kept0 : kept1)[kt >> 5] >> (kt & 31)) & 1u) != 0;
       const bool beyond = j0 > min(r0 + 31, N - 1);
@@ -291,7 +335,7 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
       const int lim = cnt - 1 - 4 * gg;
       km = lim < 0 ? 0ull : (lim >= 63 ? ~0ull : ((2ull << lim) - 1ull));
       needmask = true;
-      active = __any(cnt > 0);
+      active = cwave > gi * BK;
     }
     if (!active) continue;
     if constexpr (STATS) {
@@ -305,6 +349,7 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
     }
 
     // ---- S^T = K Q^T : lane = query (q), accumulator r of half hf <-> key 32hf + 8(r/4) + 4gg + r%4
+    const uint16_t *Kt = Ks[cur];
     f32x16 sacc[2];
 #pragma unroll
     for (int hf = 0; hf < 2; ++hf) {
@@ -312,7 +357,7 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
       for (int r = 0; r < 16; ++r) sacc[hf][r] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 a = *(const bf16x8 *)&Ks[(32 * hf + q) * KS + 16 * ks + 8 * gg];
+        const bf16x8 a = *(const bf16x8 *)&Kt[koff[ks] + 32 * hf * 128];
         sacc[hf] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], sacc[hf], 0, 0, 0);
       }
     }
@@ -357,9 +402,7 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
       }
     l_run += psum;
     // ---- O^T += V^T P^T : k-slot (gg,e) of step (hf,u) <-> key 32hf + 16u + 8(e/4) + 4gg + e%4 ----
-    // V sits row-major [key][d] in LDS; ds_read_b64_tr_b16 hands each lane four consecutive keys
-    // of ONE d column: within 16 lanes, source lane r supplies the 8-byte piece (key r/4,
-    // d 4(r%4)..+3) and receives (keys 0..3, d r).  Two such reads form the A operand.
+    const uint16_t *Vt = Vs[cur];
 #pragma unroll
     for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
@@ -369,9 +412,9 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
         for (int e = 0; e < 8; ++e) pb[e] = (__bf16)sacc[hf][8 * u + e];
 #pragma unroll
         for (int db = 0; db < 4; ++db) {
-          const uint16_t *src = vtr + (32 * hf + 16 * u) * KSV + 32 * db;
+          const uint16_t *src = Vt + voff[db] + (32 * hf + 16 * u) * 128;
           const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)src);
-          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(src + 8 * KSV));
+          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(src + 8 * 128));
           const s16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
           oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pb,
                                                              oacc[db], 0, 0, 0);
@@ -396,6 +439,7 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
   }
 }
 
+#undef SA_STORE_TILE
 #undef SA_ISSUE_LOADS
 
 }  // namespace
@@ -418,6 +462,8 @@ hipError_t launch_sparse_prefill(const Shape &sh, const Workspace &ws, const uin
   a.q_hs = sh.q_hs; a.q_rs = sh.q_rs; a.kv_hs = sh.kv_hs; a.kv_rs = sh.kv_rs;
   a.c = sh.scale * 1.4426950408889634f;
   a.counters = counters;
+  a.Kg = ws.kg; a.Vg = ws.vg; a.kvg_rows = (sh.k_v + BK - 1) / BK * BK;
+  gather_columns_kernel<<<dim3(a.kvg_rows / BK, sh.Hq), 256, 0, st>>>(a);
   if (counters)
     sparse_prefill_kernel<true><<<a.nT * sh.Hq, 256, 0, st>>>(a);
   else

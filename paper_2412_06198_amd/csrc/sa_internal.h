@@ -30,6 +30,7 @@ struct Workspace {
   float2 *part;                   // [Hq][nchunks][64] partial (max, sum) of the window rows
   float2 *stats;                  // [Hq][64] (max * scale*log2e, 1/sum)
   uint32_t *offbits, *colbits;    // [Hq][N/32] membership bitmaps of offs / cols
+  uint16_t *kg, *vg;              // [Hq][roundup64(k_v)][128] gathered K / V rows of the selected columns
 };
 
 hipError_t launch_estimate(const Shape &sh, const Workspace &ws, const uint16_t *Q,
