@@ -13,7 +13,7 @@ struct sa_ctx {
   sa::Workspace ws;
   bool have_ws;
   size_t ws_bytes;
-  size_t off[8];
+  size_t off[9];
   char err[256];
 };
 
@@ -47,6 +47,7 @@ void carve(sa_ctx *c) {
   const size_t kvg = (size_t)s.Hq * ((s.k_v + 63) / 64 * 64) * sa::kHeadDim * 2;
   c->off[6] = o; o += align256(kvg);
   c->off[7] = o; o += align256(kvg);
+  c->off[8] = o; o += 256;
   c->ws_bytes = o;
 }
 
@@ -125,6 +126,17 @@ sa_status sa_create(const sa_config *cfg, sa_ctx **out) {
     delete c;
     return SA_ERR_UNSUPPORTED;
   }
+  {
+    // the attention kernel is persistent: it launches two workgroups per compute unit.
+    // Without a usable device (a CPU-only build check) fall back to the MI355X count.
+    int dev = 0, ncu = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || ncu <= 0) {
+      (void)hipGetLastError();
+      ncu = 256;
+    }
+    s.n_cu = ncu;
+  }
   s.scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)sa::kHeadDim);
   c->have_ws = false;
   c->err[0] = 0;
@@ -174,6 +186,7 @@ sa_status sa_set_workspace(sa_ctx *c, void *dev, size_t bytes) {
   c->ws.colbits = (uint32_t *)(p + c->off[5]);
   c->ws.kg = (uint16_t *)(p + c->off[6]);
   c->ws.vg = (uint16_t *)(p + c->off[7]);
+  c->ws.queue = (unsigned int *)(p + c->off[8]);
   c->have_ws = true;
   return SA_OK;
 }

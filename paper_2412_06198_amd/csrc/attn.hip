@@ -36,14 +36,18 @@ struct AttnArgs {
   int Hq, Hkv, g, N, b, nb, nT, k_v, k_s, cap_b;
   int64_t q_hs, q_rs, kv_hs, kv_rs;
   float c;  // softmax scale * log2(e)
+  unsigned int *queue;           // [8] work-queue heads, zeroed by index_bitmaps_kernel
+  int n_items;
   unsigned long long *counters;  // instrumentation only: {active wave-tiles, kept (query,key) pairs}
 };
 
 // Membership bitmaps of the selected columns and diagonal offsets, one block per head.
 __global__ void index_bitmaps_kernel(const int32_t *n_cols, const int32_t *cols,
                                      const int32_t *n_offs, const int32_t *offs, int k_v, int k_s,
-                                     int N, uint32_t *colbits, uint32_t *offbits) {
+                                     int N, uint32_t *colbits, uint32_t *offbits,
+                                     unsigned int *queue) {
   const int h = blockIdx.x, nw = N / 32;
+  if (h == 0 && threadIdx.x < 8) queue[threadIdx.x] = 0u;
   for (int i = threadIdx.x; i < nw; i += blockDim.x) {
     colbits[(size_t)h * nw + i] = 0u;
     offbits[(size_t)h * nw + i] = 0u;
@@ -111,9 +115,29 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform for the compiler too
   const int q = lane & 31, gg = lane >> 5;
 
-  // work item: KV heads rotate fastest so that one XCD keeps one KV head in its L2;
-  // the longest (last) row blocks start first.
-  const int id = blockIdx.x;
+  // Persistent workgroups pull (head, row block) items from eight queues, one per XCD
+  // (consecutive workgroup ids land on consecutive XCDs): item id = queue + 8*k.  KV heads
+  // rotate fastest in the item id, so a queue - and with it an XCD and its L2 - stays on one
+  // KV head while Hkv is a multiple of 8.  The longest (last) row blocks come first.  A
+  // workgroup whose own queue is empty takes from the others, then exits.
+  __shared__ int s_item;
+  const int home = blockIdx.x & 7;
+  for (;;) {
+  __syncthreads();  // previous item fully retired: LDS work lists and tiles may be reused
+  if (tid == 0) {
+    int item = -1;
+    for (int qq = 0; qq < 8 && item < 0; ++qq) {
+      const int qn = (home + qq) & 7;
+      if (qn + 8 * (int)__hip_atomic_load(&p.queue[qn], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= p.n_items)
+        continue;
+      const int k = (int)atomicAdd(&p.queue[qn], 1u);
+      if (qn + 8 * k < p.n_items) item = qn + 8 * k;
+    }
+    s_item = item;
+  }
+  __syncthreads();
+  const int id = __builtin_amdgcn_readfirstlane(s_item);
+  if (id < 0) break;
   const int kvh = id % p.Hkv;
   const int rest = id / p.Hkv;
   const int h = kvh * p.g + rest % p.g;
@@ -437,6 +461,7 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
         *(uint2 *)(orow + 32 * db + 8 * rb + 4 * gg) = o.u;
       }
   }
+  }  // work-queue loop
 }
 
 #undef SA_STORE_TILE
@@ -448,7 +473,7 @@ hipError_t launch_sparse_prefill(const Shape &sh, const Workspace &ws, const uin
                                  const uint16_t *K, const uint16_t *V, sa_index idx, uint16_t *O,
                                  unsigned long long *counters, hipStream_t st) {
   index_bitmaps_kernel<<<sh.Hq, 256, 0, st>>>(idx.n_cols, idx.cols, idx.n_offs, idx.offs, sh.k_v,
-                                              sh.k_s, sh.N, ws.colbits, ws.offbits);
+                                              sh.k_s, sh.N, ws.colbits, ws.offbits, ws.queue);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   AttnArgs a;
@@ -464,10 +489,13 @@ hipError_t launch_sparse_prefill(const Shape &sh, const Workspace &ws, const uin
   a.counters = counters;
   a.Kg = ws.kg; a.Vg = ws.vg; a.kvg_rows = (sh.k_v + BK - 1) / BK * BK;
   gather_columns_kernel<<<dim3(a.kvg_rows / BK, sh.Hq), 256, 0, st>>>(a);
+  a.queue = ws.queue;
+  a.n_items = a.nT * sh.Hq;
+  const int grid = a.n_items < 2 * sh.n_cu ? a.n_items : 2 * sh.n_cu;  // two resident workgroups per CU
   if (counters)
-    sparse_prefill_kernel<true><<<a.nT * sh.Hq, 256, 0, st>>>(a);
+    sparse_prefill_kernel<true><<<grid, 256, 0, st>>>(a);
   else
-    sparse_prefill_kernel<false><<<a.nT * sh.Hq, 256, 0, st>>>(a);
+    sparse_prefill_kernel<false><<<grid, 256, 0, st>>>(a);
   return hipGetLastError();
 }
 

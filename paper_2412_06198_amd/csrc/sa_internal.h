@@ -21,6 +21,7 @@ struct Shape {
   int k_v, k_s, k_b, cap_b, sink, local;
   int probe_v, probe_s, lift_num, lift_den;
   int nchunks;                    // ceil(N / kChunk)
+  int n_cu;                       // compute units of the device the context was created on
   int64_t q_hs, q_rs, kv_hs, kv_rs;
   float scale;
 };
@@ -30,6 +31,7 @@ struct Workspace {
   float2 *part;                   // [Hq][nchunks][64] partial (max, sum) of the window rows
   float2 *stats;                  // [Hq][64] (max * scale*log2e, 1/sum)
   uint32_t *offbits, *colbits;    // [Hq][N/32] membership bitmaps of offs / cols
+  unsigned int *queue;            // [8] work-queue heads of the attention kernel
   uint16_t *kg, *vg;              // [Hq][roundup64(k_v)][128] gathered K / V rows of the selected columns
 };
 
