@@ -111,9 +111,7 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
   __shared__ int s_ntiles;
   __shared__ int s_cmax[4];
 
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform for the compiler too
-  const int q = lane & 31, gg = lane >> 5;
+  const int wv = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);  // wave-uniform for the compiler too
 
   // Persistent workgroups pull (head, row block) items from eight queues, one per XCD
   // (consecutive workgroup ids land on consecutive XCDs): item id = queue + 8*k.  KV heads
@@ -123,6 +121,11 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
   __shared__ int s_item;
   const int home = blockIdx.x & 7;
   for (;;) {
+  // Lane-derived constants are recomputed per item from an opaque copy of the thread id:
+  // hoisted out of this loop they would stay live across every phase and spill.
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));
+  const int lane = tid & 63, q = lane & 31, gg = lane >> 5;
   __syncthreads();  // previous item fully retired: LDS work lists and tiles may be reused
   if (tid == 0) {
     int item = -1;
@@ -180,15 +183,6 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
           }
         }
       }
-    }
-    const int no = min(max(p.n_offs[h], 0), p.k_s);
-    for (int e = tid; e < no; e += 256) {
-      const int o = p.offs[(size_t)h * p.k_s + e];
-      if (o < 0) continue;
-      const int hi = ilast - o;
-      if (hi < 0) continue;
-      const int lo = max(i0 - o, 0);
-      for (int kt = lo / BK; kt <= hi / BK; ++kt) atomicOr(&need[kt >> 5], 1u << (kt & 31));
     }
   }
   __syncthreads();
@@ -292,22 +286,25 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
     *(uint4 *)&Vs[buf][vst + 32 * 128] = v2; *(uint4 *)&Vs[buf][vst + 48 * 128] = v3;        \
   }
 
-  // per-lane LDS offsets (16-bit elements) of the operand reads
-  //   K (A of S^T): row 32hf + q, chunk 2ks + gg  ->  b128
-  int koff[8];
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks) koff[ks] = kswz(q, 2 * ks + gg);  // + 32hf*128 : (row & 15) unchanged
+  // per-lane LDS byte offsets of the operand reads.  The swizzles only touch address bits 4..7,
+  // so every access is (one per-lane base) XOR (a compile-time constant):
+  //   K (A of S^T): row 32hf + q, chunk 2ks + gg -> b128 at kbase ^ ((2ks + gg) << 4) + 32hf*256
   //   V (A of O^T, transposing read): within 16 lanes, source lane r supplies the 8-byte piece
-  //   (key r/4, d 4(r%4)..+3) and receives (keys 0..3, d r); lanes 16..31 take d 16..31.
+  //   (key r/4, d 4(r%4)..+3) and receives (keys 0..3, d r); lanes 16..31 take d 16..31:
+  //   row 4gg + r/4 (+ multiples of 4), chunk 4db + 2grp + (r%4)/2 -> b64 at vbase ^ (db << 6)
   typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-  int voff[4];
+  const unsigned kbase = (unsigned)(q * 256) | (unsigned)((q & 15) << 4);
+  unsigned vbase;
   {
     const int r = lane & 15, grp = (lane >> 4) & 1;
-    const int row = 4 * gg + (r >> 2);  // + 32hf + 16u + 8x : multiples of 4 keep (row & 3)
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-      voff[db] = vswz(row, 4 * db + 2 * grp + ((r & 3) >> 1)) + 4 * (r & 1);
+    const int row = 4 * gg + (r >> 2);
+    vbase = (unsigned)(row * 256) | (unsigned)(((2 * grp + ((r & 3) >> 1)) ^ ((row & 3) << 2)) << 4) |
+            (unsigned)((r & 1) << 3);
   }
+#define SA_KFRAG(tile, hf, ks) \
+  (*(const bf16x8 *)((const char *)(tile) + ((kbase ^ (unsigned)((2 * (ks) + gg) << 4)) + (hf) * 32 * 256)))
+#define SA_VTR(tile, db, key0) \
+  __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)((const char *)(tile) + ((vbase ^ (unsigned)((db) << 6)) + (key0) * 256)))
 
   if (ntot > 0) {
     SA_ISSUE_LOADS(0);
@@ -331,27 +328,14 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
       const int j0 = kt * BK;
       const bool bk = (((wv < 2 ? kept0 : kept1)[kt >> 5] >> (kt & 31)) & 1u) != 0;
       const bool beyond = j0 > min(r0 + 31, N - 1);
-      uint64_t dwin_lo = 0, dwin_hi = 0;  // 95-bit window of kept offsets, bit k <-> offset r0-j0-63+k
-      if (has_offs && !bk && !beyond) {
-        const int s0 = r0 - j0 - 63;
-        dwin_lo = bits_window64(offbm, N / 32, s0);
-        dwin_hi = bits_window64(offbm, N / 32, s0 + 64) & 0x7FFFFFFFull;
-      }
-      active = !beyond && (bk || (dwin_lo | dwin_hi) != 0);
+      active = !beyond && bk;
       const uint64_t vm = has_cols ? ((uint64_t)colbm[2 * kt] | ((uint64_t)colbm[2 * kt + 1] << 32)) : 0ull;
-      needmask = !(bk && vm == 0 && j0 + 63 <= r0);
+      needmask = !(vm == 0 && j0 + 63 <= r0);
       km = ~0ull;
       if (active && needmask) {
         const int lim = iq - j0 - 4 * gg;  // causal: slot c kept iff c <= lim
         const uint64_t cm = lim < 0 ? 0ull : (lim >= 63 ? ~0ull : ((2ull << lim) - 1ull));
-        km = cm & ~(vm >> (4 * gg));
-        if (!bk) {
-          // offset of (query q, slot c) sits at window bit q - 4gg + 63 - c = B - c, B in [59,94]:
-          // shift so that it lands at bit 59 - c, then reverse to bit c.
-          const int sh = q - 4 * gg + 4;  // B - 59, in [0,35]
-          const uint64_t y = sh ? ((dwin_lo >> sh) | (dwin_hi << (64 - sh))) : dwin_lo;
-          km &= __brevll(y) >> 4;
-        }
+        km = cm & ~(vm >> (4 * gg));  // selected columns are served by the gather tiles
       }
     } else {
       const int gi = t - ntr;
@@ -367,7 +351,7 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
       unsigned long long kept = iq < N ? (unsigned long long)__popcll(km & 0x0F0F0F0F0F0F0F0Full) : 0ull;
       for (int d = 32; d >= 1; d >>= 1) kept += __shfl_xor(kept, d);
       if (lane == 0) {
-        atomicAdd(&p.counters[0], 1ull);
+        atomicAdd(&p.counters[0], 2ull);
         atomicAdd(&p.counters[1], kept);
       }
     }
@@ -381,7 +365,7 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
       for (int r = 0; r < 16; ++r) sacc[hf][r] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 a = *(const bf16x8 *)&Kt[koff[ks] + 32 * hf * 128];
+        const bf16x8 a = SA_KFRAG(Kt, hf, ks);
         sacc[hf] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], sacc[hf], 0, 0, 0);
       }
     }
@@ -436,14 +420,159 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
         for (int e = 0; e < 8; ++e) pb[e] = (__bf16)sacc[hf][8 * u + e];
 #pragma unroll
         for (int db = 0; db < 4; ++db) {
-          const uint16_t *src = Vt + voff[db] + (32 * hf + 16 * u) * 128;
-          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)src);
-          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(src + 8 * 128));
+          const s16x4 lo = SA_VTR(Vt, db, 32 * hf + 16 * u);
+          const s16x4 hi = SA_VTR(Vt, db, 32 * hf + 16 * u + 8);
           const s16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
           oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pb,
                                                              oacc[db], 0, 0, 0);
         }
       }
+  }
+
+  // ---- selected diagonals: one 32-key tile per (wave, offset), no workgroup barriers -----------
+  // For offset o the 32 queries of this wave need the 32 keys r0-o .. r0-o+31, and in
+  // S^T = K Q^T (32 keys x 32 queries) the wanted entries are the main diagonal.  K goes from
+  // global memory straight into the A operand; V passes through a wave-private LDS tile for
+  // the transposing read.  An entry is dropped when its key block is kept by the CSR or its
+  // key is a selected column: those tiles already counted it.
+  __syncthreads();  // all waves are done with the shared tiles: reuse them as 4 private V tiles
+  if (has_offs && r0 < N) {
+    const int32_t *__restrict__ offp = p.offs + (size_t)h * p.k_s;
+    const int no = min(max(p.n_offs[h], 0), p.k_s);
+    const int rmax = min(r0 + 31, N - 1);
+    int nd = 0;  // offsets are ascending: the usable ones (o <= last row of the wave) come first
+    while (nd < no && offp[nd] >= 0 && offp[nd] <= rmax) ++nd;
+    int dl = lane;
+    asm volatile("" : "+v"(dl));  // this phase's lane constants are born here, not before the tile loop
+    const int q = dl & 31, gg = dl >> 5, lane = dl;
+    uint16_t *Vw = Vs[wv >> 1] + (wv & 1) * (32 * 128);
+    // the Q fragments move to the (now idle) K buffers: 8 KB per wave, read back one k-step at a
+    // time, so that their 32 registers can stage the next diagonal's K and V instead
+    uint16_t *Qw0 = Ks[wv >> 1] + (wv & 1) * (32 * 128);
+    unsigned qlane = lane * 8;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) *(bf16x8 *)&Qw0[qlane + ks * 512] = qf[ks];
+    const int rstar = 4 * (q >> 3) + (q & 3);        // register of S^T that holds key_local == q
+    const bool holder = gg == ((q >> 2) & 1);        // ... in this half of the lane pair
+    const int vrow = lane >> 4, vch = lane & 15;     // V staging: rows vrow+4n, 16-byte chunk vch
+    const int vdst = vswz(vrow, vch);                // rows +4n keep (row & 3)
+    const uint16_t *Kq = Kh + 8 * gg, *Vq = Vh + 8 * vch;
+    bf16x8 ka0, ka1, ka2, ka3, ka4, ka5, ka6, ka7;
+    uint4 vs0, vs1, vs2, vs3, vs4, vs5, vs6, vs7;
+#define SA_DIAG_LOAD_K(o)                                                          \
+  {                                                                                \
+    const int jr = min(max(r0 - (o) + q, 0), N - 1);                               \
+    const uint16_t *kr = Kq + (size_t)jr * p.kv_rs;                                \
+    ka0 = *(const bf16x8 *)(kr); ka1 = *(const bf16x8 *)(kr + 16);                 \
+    ka2 = *(const bf16x8 *)(kr + 32); ka3 = *(const bf16x8 *)(kr + 48);            \
+    ka4 = *(const bf16x8 *)(kr + 64); ka5 = *(const bf16x8 *)(kr + 80);            \
+    ka6 = *(const bf16x8 *)(kr + 96); ka7 = *(const bf16x8 *)(kr + 112);           \
+  }
+#define SA_DIAG_LOAD_V(o)                                                          \
+  {                                                                                \
+    const int jb_ = r0 - (o);                                                      \
+    if (jb_ >= 0 && jb_ + 31 < N) {                                                \
+      const uint16_t *vp = Vq + (size_t)(jb_ + vrow) * p.kv_rs;                    \
+      const size_t st = 4 * (size_t)p.kv_rs;                                       \
+      vs0 = *(const uint4 *)(vp); vs1 = *(const uint4 *)(vp + st);                 \
+      vs2 = *(const uint4 *)(vp + 2 * st); vs3 = *(const uint4 *)(vp + 3 * st);    \
+      vs4 = *(const uint4 *)(vp + 4 * st); vs5 = *(const uint4 *)(vp + 5 * st);    \
+      vs6 = *(const uint4 *)(vp + 6 * st); vs7 = *(const uint4 *)(vp + 7 * st);    \
+    } else {                                                                       \
+      vs0 = *(const uint4 *)SA_VROW(jb_, 0); vs1 = *(const uint4 *)SA_VROW(jb_, 1); \
+      vs2 = *(const uint4 *)SA_VROW(jb_, 2); vs3 = *(const uint4 *)SA_VROW(jb_, 3); \
+      vs4 = *(const uint4 *)SA_VROW(jb_, 4); vs5 = *(const uint4 *)SA_VROW(jb_, 5); \
+      vs6 = *(const uint4 *)SA_VROW(jb_, 6); vs7 = *(const uint4 *)SA_VROW(jb_, 7); \
+    }                                                                              \
+  }
+#define SA_VROW(jb, n) (Vq + (size_t)min(max((jb) + vrow + 4 * (n), 0), N - 1) * p.kv_rs)
+    if (nd > 0) {
+      const int o0 = __builtin_amdgcn_readfirstlane(offp[0]);
+      SA_DIAG_LOAD_K(o0);
+      SA_DIAG_LOAD_V(o0);
+    }
+    for (int e = 0; e < nd; ++e) {
+      const int o = __builtin_amdgcn_readfirstlane(offp[e]);
+      const int onext = __builtin_amdgcn_readfirstlane(offp[min(e + 1, nd - 1)]);
+      const int jb = r0 - o;
+      asm volatile("" : "+v"(qlane));  // keeps the Q reads inside the loop (no hoisting into 32 registers)
+      const uint16_t *Qw = Qw0 + qlane;
+      *(uint4 *)&Vw[vdst] = vs0; *(uint4 *)&Vw[vdst + 4 * 128] = vs1;
+      *(uint4 *)&Vw[vdst + 8 * 128] = vs2; *(uint4 *)&Vw[vdst + 12 * 128] = vs3;
+      *(uint4 *)&Vw[vdst + 16 * 128] = vs4; *(uint4 *)&Vw[vdst + 20 * 128] = vs5;
+      *(uint4 *)&Vw[vdst + 24 * 128] = vs6; *(uint4 *)&Vw[vdst + 28 * 128] = vs7;
+      if (e + 1 < nd) SA_DIAG_LOAD_V(onext);
+      f32x16 sd;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sd[r] = 0.f;
+      sd = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka0, *(const bf16x8 *)&Qw[0 * 512], sd, 0, 0, 0);
+      sd = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka1, *(const bf16x8 *)&Qw[1 * 512], sd, 0, 0, 0);
+      sd = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka2, *(const bf16x8 *)&Qw[2 * 512], sd, 0, 0, 0);
+      sd = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka3, *(const bf16x8 *)&Qw[3 * 512], sd, 0, 0, 0);
+      sd = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka4, *(const bf16x8 *)&Qw[4 * 512], sd, 0, 0, 0);
+      sd = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka5, *(const bf16x8 *)&Qw[5 * 512], sd, 0, 0, 0);
+      sd = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka6, *(const bf16x8 *)&Qw[6 * 512], sd, 0, 0, 0);
+      sd = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka7, *(const bf16x8 *)&Qw[7 * 512], sd, 0, 0, 0);
+      float sv = sd[0];
+#pragma unroll
+      for (int r = 1; r < 16; ++r) sv = (r == rstar) ? sd[r] : sv;
+      if (e + 1 < nd) SA_DIAG_LOAD_K(onext);
+      // validity of (query iq, key iq - o)
+      const int j = iq - o;
+      bool valid = holder && j >= 0 && iq < N;
+      {
+        const int kta = max(jb, 0) >> 6, ktb = max(jb + 31, 0) >> 6;  // the (at most two) key tiles touched
+        const uint32_t *kept = wv < 2 ? kept0 : kept1;
+        const bool ba = (kept[kta >> 5] >> (kta & 31)) & 1u, bb = (kept[ktb >> 5] >> (ktb & 31)) & 1u;
+        if (((max(j, 0) >> 6) == kta) ? ba : bb) valid = false;
+        if (has_cols) {
+          const uint32_t cw = (uint32_t)bits_window64(colbm, N / 32, jb);
+          if ((cw >> q) & 1u) valid = false;
+        }
+      }
+      if constexpr (STATS) {
+        unsigned long long kept_n = valid ? 1ull : 0ull;
+        for (int d = 32; d >= 1; d >>= 1) kept_n += __shfl_xor(kept_n, d);
+        if (lane == 0) {
+          atomicAdd(&p.counters[0], 1ull);
+          atomicAdd(&p.counters[1], kept_n);
+        }
+      }
+      float sm = valid ? sv : -INFINITY;
+      sm = fmaxf(sm, __shfl_xor(sm, 32));  // both lanes of the pair know the row's score
+      const float m_new = fmaxf(m_run, sm * p.c);
+      if (__any(m_new - m_run > 8.f)) {
+        const float alpha = __builtin_amdgcn_exp2f(m_run - ((m_new == -INFINITY) ? 0.f : m_new));
+        m_run = m_new;
+        l_run *= alpha;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+      }
+      const float m_ref = (m_run == -INFINITY) ? 0.f : m_run;
+      const float pv = valid ? __builtin_amdgcn_exp2f(__builtin_fmaf(sv, p.c, -m_ref)) : 0.f;
+      l_run += pv;
+      const __bf16 pvb = (__bf16)pv, zb = (__bf16)0.f;
+      // P^T is diagonal: slot e of k-step u is register 8u+e
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        bf16x8 pb;
+#pragma unroll
+        for (int e2 = 0; e2 < 8; ++e2) pb[e2] = (8 * u + e2 == rstar) ? pvb : zb;
+#pragma unroll
+        for (int db = 0; db < 4; ++db) {
+          const s16x4 lo = SA_VTR(Vw, db, 16 * u);
+          const s16x4 hi = SA_VTR(Vw, db, 16 * u + 8);
+          const s16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pb,
+                                                             oacc[db], 0, 0, 0);
+        }
+      }
+    }
+#undef SA_DIAG_LOAD_K
+#undef SA_DIAG_LOAD_V
+#undef SA_VROW
   }
 
   // ---- epilogue: O[iq][32db + 8(r/4) + 4gg + r%4] = oacc / l -------------------------------------
@@ -465,6 +594,8 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
 }
 
 #undef SA_STORE_TILE
+#undef SA_KFRAG
+#undef SA_VTR
 #undef SA_ISSUE_LOADS
 
 }  // namespace
