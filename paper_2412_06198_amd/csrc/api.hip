@@ -212,6 +212,8 @@ sa_status sa_build_index(sa_ctx *c, sa_scores in, const int32_t *override_host, 
   if (!in.v || !in.s || !in.blk || !out.pattern || !out.n_cols || !out.cols || !out.n_offs ||
       !out.offs || !out.rowptr || !out.blkcols)
     return fail(c, SA_ERR_INVALID_ARG, "null pointer");
+  if (((uintptr_t)in.v | (uintptr_t)in.s | (uintptr_t)in.blk) & 15)
+    return fail(c, SA_ERR_INVALID_ARG, "v, s, blk must be 16-byte aligned");
   sa::Override ov;
   for (int h = 0; h < sa::kMaxHeads; ++h) ov.pat[h] = -1;
   if (override_host)

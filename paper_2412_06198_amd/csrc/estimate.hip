@@ -169,19 +169,32 @@ __global__ __launch_bounds__(256) void window_stats_kernel(const uint16_t *Q, co
   }
 }
 
-// combine the per-chunk partials: grid Hq, 64 threads.
-__global__ void window_stats_reduce_kernel(const float2 *part, int nchunks, int w, float2 *stats) {
-  const int hq = blockIdx.x, i = threadIdx.x;
-  if (i >= w) { stats[(size_t)hq * kWin + i] = make_float2(INFINITY, 0.f); return; }
+// combine the per-chunk partials: grid Hq, 1024 threads = 16 chunk slices x 64 window rows.
+__global__ __launch_bounds__(1024) void window_stats_reduce_kernel(const float2 *part, int nchunks,
+                                                                  int w, float2 *stats) {
+  __shared__ float2 red[16][kWin];
+  const int hq = blockIdx.x, i = threadIdx.x & 63, sl = threadIdx.x >> 6;
   const float2 *p = part + (size_t)hq * nchunks * kWin + i;
-  float M = -INFINITY;
-  for (int cidx = 0; cidx < nchunks; ++cidx) M = fmaxf(M, p[(size_t)cidx * kWin].x);
-  float Z = 0.f;
-  for (int cidx = 0; cidx < nchunks; ++cidx) {
-    const float2 e = p[(size_t)cidx * kWin];
-    if (e.x != -INFINITY) Z += e.y * __builtin_amdgcn_exp2f(e.x - M);
+  float M = -INFINITY, Z = 0.f;
+  if (i < w)
+    for (int cidx = sl; cidx < nchunks; cidx += 16) {
+      const float2 e = p[(size_t)cidx * kWin];
+      if (e.x == -INFINITY) continue;
+      const float Mn = fmaxf(M, e.x);
+      Z = Z * __builtin_amdgcn_exp2f(M - Mn) + e.y * __builtin_amdgcn_exp2f(e.x - Mn);
+      M = Mn;
+    }
+  red[sl][i] = make_float2(M, Z);
+  __syncthreads();
+  if (sl == 0) {
+    if (i >= w) { stats[(size_t)hq * kWin + i] = make_float2(INFINITY, 0.f); return; }
+    float Mt = -INFINITY;
+    for (int k = 0; k < 16; ++k) Mt = fmaxf(Mt, red[k][i].x);
+    float Zt = 0.f;
+    for (int k = 0; k < 16; ++k)
+      if (red[k][i].x != -INFINITY) Zt += red[k][i].y * __builtin_amdgcn_exp2f(red[k][i].x - Mt);
+    stats[(size_t)hq * kWin + i] = make_float2(Mt, 1.0f / Zt);
   }
-  stats[(size_t)hq * kWin + i] = make_float2(M, 1.0f / Z);
 }
 
 // pass 2: grid (nchunks, Hkv, ceil(g/4)), 256 threads.
@@ -374,7 +387,7 @@ hipError_t launch_estimate(const Shape &sh, const Workspace &ws, const uint16_t 
   const float c = sh.scale * 1.4426950408889634f;
   const dim3 wgrid(sh.nchunks, sh.Hkv, (sh.g + 3) / 4);
   window_stats_kernel<<<wgrid, 256, 0, st>>>(Q, K, sh, c, ws.part, out.s);
-  window_stats_reduce_kernel<<<sh.Hq, kWin, 0, st>>>(ws.part, sh.nchunks, sh.w, ws.stats);
+  window_stats_reduce_kernel<<<sh.Hq, 1024, 0, st>>>(ws.part, sh.nchunks, sh.w, ws.stats);
   window_scores_kernel<<<wgrid, 256, 0, st>>>(Q, K, sh, c, ws.stats, out.v, out.s);
   block_mean_kernel<<<dim3(sh.nb, sh.Hq + sh.Hkv), 256, 0, st>>>(Q, K, sh, ws.qblk, ws.kblk);
   const int nt = (sh.nb + 63) / 64;
