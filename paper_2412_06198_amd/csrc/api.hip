@@ -13,7 +13,7 @@ struct sa_ctx {
   sa::Workspace ws;
   bool have_ws;
   size_t ws_bytes;
-  size_t off[9];
+  size_t off[10];
   char err[256];
 };
 
@@ -48,6 +48,7 @@ void carve(sa_ctx *c) {
   c->off[6] = o; o += align256(kvg);
   c->off[7] = o; o += align256(kvg);
   c->off[8] = o; o += 256;
+  c->off[9] = o; o += align256(sa::index_scratch_bytes(s.Hq));
   c->ws_bytes = o;
 }
 
@@ -187,6 +188,7 @@ sa_status sa_set_workspace(sa_ctx *c, void *dev, size_t bytes) {
   c->ws.kg = (uint16_t *)(p + c->off[6]);
   c->ws.vg = (uint16_t *)(p + c->off[7]);
   c->ws.queue = (unsigned int *)(p + c->off[8]);
+  c->ws.idx = (void *)(p + c->off[9]);
   c->have_ws = true;
   return SA_OK;
 }

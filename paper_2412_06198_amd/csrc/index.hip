@@ -5,34 +5,55 @@
 // Integer work only: scores are compared through their fp32 bit patterns (all
 // scores are >= +0, so the unsigned order is the numeric order), ties go to the
 // lower index, and the pattern rule sums floor(score * 2^30) in 64-bit integers.
-// One workgroup of 1024 threads per head:
-//   radix select (4 passes of 8 bits, LDS histogram) -> threshold key and the
-//   number of threshold-valued candidates to take, then an ordered compaction
-//   (wave ballots over index-ordered segments) that emits the selection
-//   ascending by index - no sort anywhere.
+//
+// Five selections run side by side for every head, so that nothing waits on the
+// pattern decision: the probe_v / probe_s best of v and s (pattern rule), the
+// k_v best columns, the k_s best diagonals, the k_b - nb best blocks.  Each is a
+// radix select in three levels (11 + 11 + 10 key bits).  Every level is a
+// launch of P workgroups per head (LDS histograms, flushed to global memory with
+// integer atomics) followed by a one-workgroup-per-head launch that reads the
+// merged histogram and fixes the next digit: kernel boundaries are the only
+// synchronisation between workgroups, no fences or spin waits.  Two more
+// launches count and then emit the selected entries in index order (wave
+// ballots), so the result is sorted without any sort.
+#include <cstddef>
+
 #include "sa_internal.h"
 
 namespace sa {
 namespace {
 
-constexpr int NT = 1024;
-constexpr int NWAVE = NT / 64;
+constexpr int BT = 256;            // threads per workgroup
+constexpr int WPB = BT / 64;       // waves per workgroup
+constexpr int kMaxParts = 64;      // workgroups per head
+constexpr int kMaxPW = kMaxParts * WPB;
 constexpr int kMaxNb = kMaxSeq / 64;
+constexpr int NSEL = 5;            // 0: v probe, 1: s probe, 2: v top k_v, 3: s top k_s, 4: blk top k_b - nb
+constexpr int L1BINS = 2048, L2BINS = 2048, L3BINS = 1024;  // 11 + 11 + 10 key bits
+
+// per-head scratch in the workspace
+struct IdxScratch {
+  alignas(16) unsigned hist1[3][L1BINS];  // level 1 per array: v, s, blk
+  alignas(16) unsigned hist2[NSEL][L2BINS];
+  alignas(16) unsigned hist3[NSEL][L3BINS];
+  unsigned long long vtot, ct, topsum[2];
+  // everything above is zeroed at the start of a call
+  unsigned prefix[NSEL], remaining[NSEL];
+  unsigned thr[NSEL], need[NSEL];
+  unsigned wgt[2][kMaxPW], weq[2][kMaxPW];  // v / s: counts per wave part, then exclusive prefixes
+  unsigned rowgt[kMaxNb], roweq[kMaxNb];    // blk: counts per row, then exclusive prefixes
+  int pattern;
+};
+constexpr size_t kZeroWords = offsetof(IdxScratch, prefix) / 4;
 
 struct IdxArgs {
-  const float *v, *s, *blk;
+  const unsigned *v, *s, *blk;     // fp32 scores as bit patterns
+  IdxScratch *scratch;
   Shape sh;
   Override ov;
   sa_index out;
-};
-
-struct Smem {
-  unsigned whist[NWAVE][256];  // one private histogram per wave: no cross-wave contention
-  unsigned hist[256];
-  unsigned wave_a[NWAVE], wave_b[NWAVE];
-  unsigned long long red64[NWAVE];
-  unsigned sel_prefix, sel_remaining;
-  unsigned rowgt[kMaxNb], roweq[kMaxNb];
+  int P, PW, seg;                  // workgroups per head, wave parts per head, keys of v / s per wave part
+  int ksel[NSEL];                  // clamped k of every selection
 };
 
 // floor(x * 2^30) of a finite fp32 x >= 0 given by its bits.
@@ -43,33 +64,6 @@ __device__ inline unsigned long long fx30(unsigned bits) {
   const int sh = e - 120;   // (e - 127) - 23 + 30
   if (sh >= 0) return sh < 40 ? (m << sh) : ~0ull;
   return (-sh) < 64 ? (m >> (-sh)) : 0ull;
-}
-
-__device__ inline unsigned long long block_sum_u64(unsigned long long x, Smem &sm) {
-  for (int d = 32; d >= 1; d >>= 1) x += __shfl_xor(x, d);
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) sm.red64[threadIdx.x >> 6] = x;
-  __syncthreads();
-  unsigned long long t = 0;
-  for (int w = 0; w < NWAVE; ++w) t += sm.red64[w];
-  return t;
-}
-
-// exclusive prefix sums of two per-thread counters over the 1024 threads
-__device__ inline void block_scan2(unsigned a, unsigned b, unsigned &ea, unsigned &eb, Smem &sm) {
-  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  unsigned ia = a, ib = b;
-  for (int d = 1; d < 64; d <<= 1) {
-    const unsigned oa = __shfl_up(ia, d), ob = __shfl_up(ib, d);
-    if (lane >= d) { ia += oa; ib += ob; }
-  }
-  __syncthreads();
-  if (lane == 63) { sm.wave_a[wv] = ia; sm.wave_b[wv] = ib; }
-  __syncthreads();
-  unsigned ba = 0, bb = 0;
-  for (int w = 0; w < wv; ++w) { ba += sm.wave_a[w]; bb += sm.wave_b[w]; }
-  ea = ba + ia - a;
-  eb = bb + ib - b;
 }
 
 // ---- candidate walks ---------------------------------------------------------------------------
@@ -90,19 +84,6 @@ __device__ inline Keys4 load4(const unsigned *p, int i, int lim, bool vec) {
   return r;
 }
 
-// whole block, order irrelevant: group g of 4 keys goes to thread g % NT
-template <class Fn>
-__device__ inline void block_visit4(const unsigned *p, int n, bool vec, Fn fn) {
-  constexpr int U = 4;
-  for (int b0 = 0; b0 < n; b0 += NT * 4 * U) {
-    Keys4 v[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) v[u] = load4(p, b0 + (u * NT + (int)threadIdx.x) * 4, n, vec);
-#pragma unroll
-    for (int u = 0; u < U; ++u) fn(v[u], b0 + (u * NT + (int)threadIdx.x) * 4, n);
-  }
-}
-
 // one wave, indices [lo,hi) in increasing groups of 256: lane l holds lo + 256g + 4l .. +3
 template <class Fn>
 __device__ inline void wave_visit4(const unsigned *p, int lo, int hi, bool vec, Fn fn) {
@@ -118,15 +99,17 @@ __device__ inline void wave_visit4(const unsigned *p, int lo, int hi, bool vec, 
   }
 }
 
-// The strictly-lower part (C < R) of every row this wave owns (R = wave, wave+16, ...), walked in
-// units of 1024 keys with the next unit's loads issued before the current one is processed:
-// short rows would otherwise expose one memory round trip each.  begin(R) / end(R) bracket a row.
+// The strictly-lower part (C < R) of the rows R = first, first + stride, ... of the nb x nb block
+// map, walked by one wave in units of 1024 keys with the next unit's loads issued before the
+// current one is processed: short rows would otherwise expose one memory round trip each.
+// begin(R) / end(R) bracket a row.
 template <class Begin, class Fn, class End>
-__device__ inline void wave_rows_visit4(const unsigned *blk, int nb, bool vec, Begin begin, Fn fn, End end) {
+__device__ inline void wave_rows_visit4(const unsigned *blk, int nb, int first, int stride, bool vec,
+                                        Begin begin, Fn fn, End end) {
   constexpr int U = 4;
-  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  int R = wv, c0 = 0;          // unit being processed
-  int Rn = wv, cn = 0;         // unit being loaded
+  const int lane = threadIdx.x & 63;
+  int R = first, c0 = 0;    // unit being processed
+  int Rn = first, cn = 0;   // unit being loaded
   Keys4 cur[U], nxt[U];
   auto load_unit = [&](Keys4 (&dst)[U], int row, int col) {
     const unsigned *p = blk + (size_t)row * nb;
@@ -135,7 +118,7 @@ __device__ inline void wave_rows_visit4(const unsigned *blk, int nb, bool vec, B
   };
   auto advance = [&](int &row, int &col) {
     col += 256 * U;
-    if (col >= row) { row += NWAVE; col = 0; }
+    if (col >= row) { row += stride; col = 0; }
   };
   if (Rn < nb) load_unit(nxt, Rn, cn);
   while (R < nb) {
@@ -150,6 +133,25 @@ __device__ inline void wave_rows_visit4(const unsigned *blk, int nb, bool vec, B
     if (c0 + 256 * U >= R) end(R);
     advance(R, c0);
   }
+}
+
+// Adds one count per valid lane to an LDS histogram.  Same-address LDS atomics are serialised
+// lane by lane, and the scores of a head share their leading bits, so the bin of the first valid
+// lane is added once with its lane count (two such peels); what is left goes one atomic per lane.
+// Must be called by all 64 lanes.
+__device__ inline void hist_add(unsigned *h, unsigned bin, bool valid) {
+#pragma unroll
+  for (int peel = 0; peel < 2; ++peel) {
+    const unsigned long long mv = __ballot(valid);
+    if (mv == 0) return;
+    const int first = __ffsll((long long)mv) - 1;
+    const unsigned b0 = __builtin_amdgcn_readlane(bin, first);
+    const bool same = valid && bin == b0;
+    const unsigned long long ms = __ballot(same);
+    if ((int)(threadIdx.x & 63) == first) atomicAdd(&h[b0], (unsigned)__popcll(ms));
+    valid = valid && !same;
+  }
+  if (valid) atomicAdd(&h[bin], 1u);
 }
 
 // Ordered emission for one 256-key group of a wave: an element is selected if its key is above the
@@ -181,323 +183,426 @@ __device__ inline void emit_group(const Keys4 &v, int i0, int lim, unsigned thr,
   erun += etot;
 }
 
-// Adds one count per valid lane to a wave-private LDS histogram.  Same-address LDS atomics are
-// serialised lane by lane, and the scores of a head share their leading bits, so the bin of the
-// first valid lane is added once with its lane count (twice: two peels); what is left goes one
-// atomic per lane.  Must be called by all 64 lanes.
-__device__ inline void hist_add(unsigned *wh, unsigned bin, bool valid) {
-#pragma unroll
-  for (int peel = 0; peel < 2; ++peel) {
-    const unsigned long long mv = __ballot(valid);
-    if (mv == 0) return;
-    const int first = __ffsll((long long)mv) - 1;
-    const unsigned b0 = __builtin_amdgcn_readlane(bin, first);  // bin of the first valid lane
-    const bool same = valid && bin == b0;
-    const unsigned long long ms = __ballot(same);
-    if ((int)(threadIdx.x & 63) == first) atomicAdd(&wh[b0], (unsigned)__popcll(ms));
-    valid = valid && !same;
+// In a histogram of nbins (a multiple of 64) counts held in LDS, the bin that holds the k-th key
+// counted from the top bin down (1 <= k <= total), and the rank of that key inside the bin.
+// One wave.
+__device__ inline void wave_find_kth(const unsigned *hist, int nbins, unsigned k, unsigned &bin,
+                                     unsigned &rank) {
+  const int lane = threadIdx.x & 63;
+  const int per = nbins / 64;  // lane l owns bins [l*per, (l+1)*per)
+  unsigned tot = 0;
+  for (int i = 0; i < per; ++i) tot += hist[lane * per + i];
+  unsigned incl = tot;  // inclusive suffix sum over lanes >= l
+  for (int d = 1; d < 64; d <<= 1) {
+    const unsigned o = __shfl_down(incl, d);
+    if (lane + d < 64) incl += o;
   }
-  if (valid) atomicAdd(&wh[bin], 1u);
+  const unsigned above = incl - tot;
+  const bool mine = above < k && k <= above + tot;
+  const unsigned long long m = __ballot(mine);
+  const int owner = m ? __ffsll((long long)m) - 1 : 0;
+  unsigned b = 0, r = 0;
+  if (lane == owner) {
+    unsigned ab = above;
+    for (int i = per - 1; i >= 0; --i) {
+      const unsigned c = hist[lane * per + i];
+      if (ab < k && k <= ab + c) { b = (unsigned)(lane * per + i); r = k - ab; break; }
+      ab += c;
+    }
+  }
+  bin = __shfl(b, owner);
+  rank = __shfl(r, owner);
 }
 
-// Radix select: finds the k-th largest key T among the candidates and how many candidates
-// equal to T belong to the k best (the ones with the lowest indices).  for_each(fn) must call
-// fn(keys, i0, lim) in wave-uniform loops for every group of four candidates this thread is
-// responsible for; k <= number of candidates.
-template <class ForEach>
-__device__ inline void radix_select(ForEach for_each, int k, unsigned &thr, unsigned &need_eq,
-                                    Smem &sm) {
-  if (k <= 0) { thr = 0xFFFFFFFFu; need_eq = 0; return; }
-  unsigned prefix = 0, mask = 0, remaining = (unsigned)k;
-  for (int pass = 3; pass >= 0; --pass) {
-    const int shift = 8 * pass;
-    __syncthreads();
-    for (int i = threadIdx.x; i < NWAVE * 256; i += NT) (&sm.whist[0][0])[i] = 0;
-    __syncthreads();
-    unsigned *wh = sm.whist[threadIdx.x >> 6];
-    for_each([&](const Keys4 &v, int i0, int lim) {
+__global__ void idx_zero_kernel(IdxScratch *scratch) {
+  unsigned *p = (unsigned *)(scratch + blockIdx.x);
+  for (size_t i = threadIdx.x; i < kZeroWords; i += blockDim.x) p[i] = 0u;
+}
+
+// ---- level histograms ------------------------------------------------------------------------------
+// LEVEL 1: bits 31..21 of every key, one histogram per array.
+// LEVEL 2: bits 20..10 of the keys whose bits 31..21 equal the selection's prefix.
+// LEVEL 3: bits  9..0 of the keys whose bits 31..10 equal the selection's prefix.
+template <int LEVEL>
+__global__ __launch_bounds__(BT) void idx_hist_kernel(IdxArgs a) {
+  constexpr int NH = LEVEL == 1 ? 3 : NSEL;
+  constexpr int BINS = LEVEL == 3 ? L3BINS : L1BINS;
+  __shared__ __attribute__((aligned(16))) unsigned hist[NH][BINS];
+  __shared__ unsigned long long red64[2][WPB];
+  const Shape &sh = a.sh;
+  const int p = blockIdx.x, h = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int N = sh.N, nb = sh.nb;
+  IdxScratch *G = a.scratch + h;
+  const unsigned *vb = a.v + (size_t)h * N, *sb = a.s + (size_t)h * N;
+  const unsigned *bb = a.blk + (size_t)h * nb * nb;
+  for (int i = tid; i < NH * BINS; i += BT) (&hist[0][0])[i] = 0u;
+  unsigned pre[NSEL];
+  bool act[NSEL];
+#pragma unroll
+  for (int q = 0; q < NSEL; ++q) {
+    pre[q] = LEVEL == 1 ? 0u : G->prefix[q];
+    act[q] = a.ksel[q] > 0;
+  }
+  __syncthreads();
+  const int gw = p * WPB + wv;
+  const int lo = min(gw * a.seg, N), hi = min(lo + a.seg, N);
+  unsigned long long vt = 0, ct = 0;
+  long long sbnd = (long long)sh.sink * sh.b;
+  if (sbnd > N) sbnd = N;
+  long long lb0 = (long long)(nb - sh.local) * sh.b;
+  if (lb0 < sbnd) lb0 = sbnd;
+
+  auto visit = [&](const Keys4 &v, int i0, int lim, int arr) {
+    // arr 0: v (selections 0, 2), 1: s (selections 1, 3), 2: blk (selection 4)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const bool ok = i0 + j < lim;
+      const unsigned key = v.k[j];
+      if (LEVEL == 1) {
+        hist_add(hist[arr], key >> 21, ok);
+      } else {
+        const unsigned hi_bits = LEVEL == 2 ? key >> 21 : key >> 10;
+        const unsigned bin = LEVEL == 2 ? (key >> 10) & 2047u : key & 1023u;
+        if (arr == 2) {
+          hist_add(hist[NH - 1], bin, ok && act[4] && hi_bits == pre[4]);
+        } else {
+          hist_add(hist[arr % NH], bin, ok && act[arr] && hi_bits == pre[arr]);
+          hist_add(hist[(arr + 2) % NH], bin, ok && act[arr + 2] && hi_bits == pre[arr + 2]);
+        }
+      }
+    }
+  };
+  wave_visit4(vb, lo, hi, true, [&](const Keys4 &v, int i0, int lim) {
+    visit(v, i0, lim, 0);
+    if (LEVEL == 1) {
 #pragma unroll
       for (int j = 0; j < 4; ++j)
-        hist_add(wh, (v.k[j] >> shift) & 255u, i0 + j < lim && (v.k[j] & mask) == prefix);
-    });
-    __syncthreads();
-    if (threadIdx.x < 256) {
-      unsigned t = 0;
-#pragma unroll
-      for (int w = 0; w < NWAVE; ++w) t += sm.whist[w][threadIdx.x];
-      sm.hist[threadIdx.x] = t;
-    }
-    __syncthreads();
-    if (threadIdx.x < 64) {
-      // lane l owns bins 4l..4l+3; suffix sums from the top bin down
-      const int l = threadIdx.x;
-      const unsigned b0 = sm.hist[4 * l], b1 = sm.hist[4 * l + 1], b2 = sm.hist[4 * l + 2],
-                     b3 = sm.hist[4 * l + 3];
-      const unsigned tot = b0 + b1 + b2 + b3;
-      unsigned incl = tot;  // inclusive suffix sum over lanes >= l
-      for (int d = 1; d < 64; d <<= 1) {
-        const unsigned o = __shfl_down(incl, d);
-        if (l + d < 64) incl += o;
-      }
-      // the bin that holds the remaining-th largest: above < remaining <= above + count
-      unsigned ab = incl - tot;
-      const unsigned bins[4] = {b3, b2, b1, b0};
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        if (ab < remaining && remaining <= ab + bins[j]) {
-          sm.sel_prefix = prefix | ((unsigned)(4 * l + 3 - j) << shift);
-          sm.sel_remaining = remaining - ab;
-        }
-        ab += bins[j];
-      }
-    }
-    __syncthreads();
-    prefix = sm.sel_prefix;
-    remaining = sm.sel_remaining;
-    mask |= 255u << shift;
-  }
-  thr = prefix;
-  need_eq = remaining;
-}
-
-// sum of fx30 over the `probe` largest keys (ties do not matter for a sum)
-__device__ inline unsigned long long top_sum(const unsigned *p, int n, int probe, Smem &sm) {
-  probe = min(probe, n);
-  if (probe <= 0) return 0ull;
-  unsigned thr, need;
-  radix_select([&](auto fn) { block_visit4(p, n, true, fn); }, probe, thr, need, sm);
-  unsigned long long acc = 0;
-  block_visit4(p, n, true, [&](const Keys4 &v, int i0, int lim) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-      if (i0 + j < lim && v.k[j] > thr) acc += fx30(v.k[j]);
-  });
-  acc = block_sum_u64(acc, sm);
-  return acc + (unsigned long long)need * fx30(thr);
-}
-
-// Ordered compaction of a 1-D candidate list: out[0..k) = selected indices ascending,
-// out[k..cap) = -1.  Each wave owns a contiguous range of indices (a multiple of 256 long).
-__device__ inline void select_1d(const unsigned *p, int n, int k, int32_t *out, int cap,
-                                 int32_t *count, Smem &sm) {
-  k = min(k, n);
-  unsigned thr, need;
-  radix_select([&](auto fn) { block_visit4(p, n, true, fn); }, k, thr, need, sm);
-  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  const int seg = ((n + NWAVE - 1) / NWAVE + 255) / 256 * 256;
-  const int lo = min(wv * seg, n), hi = min(lo + seg, n);
-  unsigned gt = 0, eq = 0;
-  wave_visit4(p, lo, hi, true, [&](const Keys4 &v, int i0, int lim) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      gt += i0 + j < lim && v.k[j] > thr;
-      eq += i0 + j < lim && v.k[j] == thr;
-    }
-  });
-  for (int d = 32; d >= 1; d >>= 1) { gt += __shfl_xor(gt, d); eq += __shfl_xor(eq, d); }
-  __syncthreads();
-  if (lane == 0) { sm.wave_a[wv] = gt; sm.wave_b[wv] = eq; }
-  __syncthreads();
-  unsigned grun = 0, erun = 0;
-  for (int w = 0; w < wv; ++w) { grun += sm.wave_a[w]; erun += sm.wave_b[w]; }
-  if (k > 0)
-    wave_visit4(p, lo, hi, true, [&](const Keys4 &v, int i0, int lim) {
-      emit_group(v, i0, lim, thr, need, grun, erun, [&](unsigned pos, int idx) { out[pos] = idx; });
-    });
-  for (int i = k + threadIdx.x; i < cap; i += NT) out[i] = -1;
-  if (threadIdx.x == 0) *count = k;
-}
-
-__global__ __launch_bounds__(NT) void build_index_kernel(IdxArgs a) {
-  __shared__ Smem sm;
-  const Shape &sh = a.sh;
-  const int h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  const int N = sh.N, nb = sh.nb, b = sh.b;
-  const unsigned *vb = (const unsigned *)(a.v + (size_t)h * N);
-  const unsigned *sb = (const unsigned *)(a.s + (size_t)h * N);
-  const unsigned *bb = (const unsigned *)(a.blk + (size_t)h * nb * nb);
-
-  // ---- pattern ---------------------------------------------------------------------------
-  int pat = a.ov.pat[h];
-  if (pat < 0) {
-    long long sbnd = (long long)sh.sink * b;
-    if (sbnd > N) sbnd = N;
-    long long lb0 = (long long)(nb - sh.local) * b;
-    if (lb0 < sbnd) lb0 = sbnd;
-    unsigned long long vt = 0, ct = 0;
-    block_visit4(vb, N, true, [&](const Keys4 &v, int i0, int lim) {
-#pragma unroll
-      for (int jj = 0; jj < 4; ++jj) {
-        const int j = i0 + jj;
-        if (j < lim) {
-          const unsigned long long f = fx30(v.k[jj]);
+        if (i0 + j < lim) {
+          const unsigned long long f = fx30(v.k[j]);
           vt += f;
-          if (j < sbnd || j >= lb0) ct += f;
+          if (i0 + j < sbnd || i0 + j >= lb0) ct += f;
         }
+    }
+  });
+  wave_visit4(sb, lo, hi, true, [&](const Keys4 &v, int i0, int lim) { visit(v, i0, lim, 1); });
+  if (act[4])
+    wave_rows_visit4(bb, nb, gw, a.PW, (nb & 3) == 0, [](int) {},
+                     [&](const Keys4 &v, int i0, int lim) { visit(v, i0, lim, 2); }, [](int) {});
+  if (LEVEL == 1) {
+    for (int d = 32; d >= 1; d >>= 1) { vt += __shfl_xor(vt, d); ct += __shfl_xor(ct, d); }
+    if (lane == 0) { red64[0][wv] = vt; red64[1][wv] = ct; }
+  }
+  __syncthreads();
+  unsigned *gh = LEVEL == 1 ? &G->hist1[0][0] : (LEVEL == 2 ? &G->hist2[0][0] : &G->hist3[0][0]);
+  for (int i = tid; i < NH * BINS; i += BT) {
+    const unsigned c = (&hist[0][0])[i];
+    if (c) atomicAdd(&gh[i], c);
+  }
+  if (LEVEL == 1 && tid == 0) {
+    unsigned long long tv = 0, tc = 0;
+    for (int w = 0; w < WPB; ++w) { tv += red64[0][w]; tc += red64[1][w]; }
+    atomicAdd(&G->vtot, tv);
+    atomicAdd(&G->ct, tc);
+  }
+}
+
+// One workgroup per head: fixes the next digit of every selection from the merged histograms.
+template <int LEVEL>
+__global__ __launch_bounds__(BT) void idx_select_kernel(IdxArgs a) {
+  constexpr int NH = LEVEL == 1 ? 3 : NSEL;
+  constexpr int BINS = LEVEL == 3 ? L3BINS : L1BINS;
+  __shared__ __attribute__((aligned(16))) unsigned hist[NH][BINS];
+  const int h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  IdxScratch *G = a.scratch + h;
+  const unsigned *gh = LEVEL == 1 ? &G->hist1[0][0] : (LEVEL == 2 ? &G->hist2[0][0] : &G->hist3[0][0]);
+  for (int i = tid * 4; i < NH * BINS; i += BT * 4)
+    *(uint4 *)&(&hist[0][0])[i] = *(const uint4 *)&gh[i];
+  __syncthreads();
+  for (int q = wv; q < NSEL; q += WPB) {  // wave w takes selections w and w + 4
+    if (a.ksel[q] <= 0) {
+      if (LEVEL == 3 && lane == 0) { G->thr[q] = 0xFFFFFFFFu; G->need[q] = 0u; }
+      continue;
+    }
+    const unsigned *hsel = LEVEL == 1 ? hist[(q == 4 ? 2 : (q & 1)) % NH] : hist[q % NH];
+    const unsigned pre = LEVEL == 1 ? 0u : G->prefix[q];
+    const unsigned k = LEVEL == 1 ? (unsigned)a.ksel[q] : G->remaining[q];
+    unsigned bin, rank;
+    wave_find_kth(hsel, BINS, k, bin, rank);
+    if (lane == 0) {
+      if (LEVEL == 1) {
+        G->prefix[q] = bin;
+        G->remaining[q] = rank;
+      } else if (LEVEL == 2) {
+        G->prefix[q] = (pre << 11) | bin;
+        G->remaining[q] = rank;
+      } else {
+        G->thr[q] = (pre << 10) | bin;
+        G->need[q] = rank;
       }
+    }
+  }
+}
+
+// ---- counts, pattern, prefixes ---------------------------------------------------------------------
+__global__ __launch_bounds__(BT) void idx_count_kernel(IdxArgs a) {
+  __shared__ unsigned long long red64[2][WPB];
+  const Shape &sh = a.sh;
+  const int p = blockIdx.x, h = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int N = sh.N, nb = sh.nb;
+  IdxScratch *G = a.scratch + h;
+  const unsigned *vb = a.v + (size_t)h * N, *sb = a.s + (size_t)h * N;
+  const unsigned *bb = a.blk + (size_t)h * nb * nb;
+  unsigned thr[NSEL], need[NSEL];
+#pragma unroll
+  for (int q = 0; q < NSEL; ++q) { thr[q] = G->thr[q]; need[q] = G->need[q]; }
+  const int gw = p * WPB + wv;
+  const int lo = min(gw * a.seg, N), hi = min(lo + a.seg, N);
+  for (int arr = 0; arr < 2; ++arr) {
+    unsigned gt = 0, eq = 0;
+    unsigned long long ts = 0;
+    const unsigned tp = thr[arr], tk = thr[arr + 2];
+    wave_visit4(arr ? sb : vb, lo, hi, true, [&](const Keys4 &v, int i0, int lim) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (i0 + j < lim) {
+          gt += v.k[j] > tk;
+          eq += v.k[j] == tk;
+          if (v.k[j] > tp) ts += fx30(v.k[j]);
+        }
     });
-    vt = block_sum_u64(vt, sm);
-    ct = block_sum_u64(ct, sm);
-    unsigned long long E = 0, ET = 0;
-    for (int i = 0; i < sh.w; ++i) {
-      const long long qi1 = (long long)N - sh.w + i + 1;
-      E += (unsigned long long)qi1;
-      ET += (unsigned long long)(qi1 < sbnd ? qi1 : sbnd);
-      if (qi1 > lb0) ET += (unsigned long long)(qi1 - lb0);
+    for (int d = 32; d >= 1; d >>= 1) {
+      gt += __shfl_xor(gt, d); eq += __shfl_xor(eq, d); ts += __shfl_xor(ts, d);
     }
-    typedef unsigned __int128 u128;
-    if ((u128)sh.lift_den * ct * E >= (u128)sh.lift_num * vt * ET) {
-      pat = SA_TRIANGULAR;
-    } else {
-      const unsigned long long sv = top_sum(vb, N, sh.probe_v, sm);
-      const unsigned long long ss = top_sum(sb, N, sh.probe_s, sm);
-      if ((u128)sh.lift_den * (sv + ss) * E >=
-          (u128)sh.lift_num * vt * (unsigned long long)(sh.probe_v + sh.probe_s) *
-              (unsigned long long)sh.w)
-        pat = SA_INTERVAL_SLASH;
-      else
-        pat = SA_BLOCK_CLUSTER;
+    if (lane == 0) { G->wgt[arr][gw] = gt; G->weq[arr][gw] = eq; red64[arr][wv] = ts; }
+  }
+  {
+    unsigned gt = 0, eq = 0;
+    wave_rows_visit4(
+        bb, nb, gw, a.PW, (nb & 3) == 0, [&](int) { gt = 0; eq = 0; },
+        [&](const Keys4 &v, int i0, int lim) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            gt += i0 + j < lim && v.k[j] > thr[4];
+            eq += i0 + j < lim && v.k[j] == thr[4];
+          }
+        },
+        [&](int R) {
+          unsigned g2 = gt, e2 = eq;
+          for (int d = 32; d >= 1; d >>= 1) { g2 += __shfl_xor(g2, d); e2 += __shfl_xor(e2, d); }
+          if (lane == 0) { G->rowgt[R] = g2; G->roweq[R] = e2; }
+        });
+  }
+  __syncthreads();
+  if (tid < 2) {
+    unsigned long long t = 0;
+    for (int w = 0; w < WPB; ++w) t += red64[tid][w];
+    atomicAdd(&G->topsum[tid], t);
+  }
+}
+
+// One workgroup per head: pattern decision, prefixes of the per-part and per-row counts, rowptr.
+__global__ __launch_bounds__(BT) void idx_scan_kernel(IdxArgs a) {
+  __shared__ unsigned s_scan[BT];
+  __shared__ unsigned s_scan2[BT];
+  __shared__ int s_pat;
+  const Shape &sh = a.sh;
+  const int h = blockIdx.x, tid = threadIdx.x;
+  const int N = sh.N, nb = sh.nb;
+  IdxScratch *G = a.scratch + h;
+  unsigned thr[NSEL], need[NSEL];
+#pragma unroll
+  for (int q = 0; q < NSEL; ++q) { thr[q] = G->thr[q]; need[q] = G->need[q]; }
+  // ---- pattern of the head (caller's override, else the integer lift tests) --------------------
+  if (tid == 0) {
+    int pat = a.ov.pat[h];
+    if (pat < 0) {
+      long long sbnd = (long long)sh.sink * sh.b;
+      if (sbnd > N) sbnd = N;
+      long long lb0 = (long long)(nb - sh.local) * sh.b;
+      if (lb0 < sbnd) lb0 = sbnd;
+      unsigned long long E = 0, ET = 0;
+      for (int i = 0; i < sh.w; ++i) {
+        const long long qi1 = (long long)N - sh.w + i + 1;
+        E += (unsigned long long)qi1;
+        ET += (unsigned long long)(qi1 < sbnd ? qi1 : sbnd);
+        if (qi1 > lb0) ET += (unsigned long long)(qi1 - lb0);
+      }
+      const unsigned long long vt = G->vtot, ct = G->ct;
+      typedef unsigned __int128 u128;
+      if ((u128)sh.lift_den * ct * E >= (u128)sh.lift_num * vt * ET) {
+        pat = SA_TRIANGULAR;
+      } else {
+        // sum over the probe best = sum over keys above the threshold + ties at the threshold
+        const unsigned long long sv =
+            a.ksel[0] > 0 ? G->topsum[0] + (unsigned long long)need[0] * fx30(thr[0]) : 0ull;
+        const unsigned long long ss =
+            a.ksel[1] > 0 ? G->topsum[1] + (unsigned long long)need[1] * fx30(thr[1]) : 0ull;
+        if ((u128)sh.lift_den * (sv + ss) * E >=
+            (u128)sh.lift_num * vt * (unsigned long long)(sh.probe_v + sh.probe_s) * (unsigned long long)sh.w)
+          pat = SA_INTERVAL_SLASH;
+        else
+          pat = SA_BLOCK_CLUSTER;
+      }
     }
+    G->pattern = pat;
+    a.out.pattern[h] = pat;
+    s_pat = pat;
   }
-  if (tid == 0) a.out.pattern[h] = pat;
-
-  // ---- columns and diagonals (Interval-Slash only) ------------------------------------------
-  int32_t *cols = a.out.cols + (size_t)h * sh.k_v;
-  int32_t *offs = a.out.offs + (size_t)h * sh.k_s;
-  if (pat == SA_INTERVAL_SLASH) {
-    select_1d(vb, N, sh.k_v, cols, sh.k_v, a.out.n_cols + h, sm);
-    select_1d(sb, N, sh.k_s, offs, sh.k_s, a.out.n_offs + h, sm);
-  } else {
-    for (int i = tid; i < sh.k_v; i += NT) cols[i] = -1;
-    for (int i = tid; i < sh.k_s; i += NT) offs[i] = -1;
-    if (tid == 0) { a.out.n_cols[h] = 0; a.out.n_offs[h] = 0; }
+  // ---- exclusive prefixes of the wave-part counts of v and s (PW <= 256 = one per thread) --------
+  for (int arr = 0; arr < 2; ++arr) {
+    __syncthreads();
+    s_scan[tid] = tid < a.PW ? G->wgt[arr][tid] : 0u;
+    s_scan2[tid] = tid < a.PW ? G->weq[arr][tid] : 0u;
+    __syncthreads();
+    unsigned pg = 0, pe = 0;
+    for (int t = 0; t < tid; ++t) { pg += s_scan[t]; pe += s_scan2[t]; }
+    if (tid < a.PW) { G->wgt[arr][tid] = pg; G->weq[arr][tid] = pe; }
   }
+  __syncthreads();
+  const int pat = s_pat;
+  // ---- row prefixes: thread t owns RP consecutive rows (nb <= kMaxNb) ------------------------------
+  constexpr int RP = kMaxNb / BT;
+  __syncthreads();
+  unsigned g16[RP], e16[RP], gs = 0, es = 0;
+#pragma unroll
+  for (int j = 0; j < RP; ++j) {
+    const int R = RP * tid + j;
+    unsigned g = 0, e = 0;
+    if (R < nb) {
+      if (pat == SA_BLOCK_CLUSTER) {
+        g = G->rowgt[R];
+        e = G->roweq[R];
+      } else if (pat == SA_TRIANGULAR) {
+        const int bs = max(R - sh.local + 1, 0);  // row R keeps C < min(sink, band start) and the band
+        g = (unsigned)(min(sh.sink, bs) + (R - bs + 1));
+      } else {
+        g = 1u;
+      }
+    }
+    g16[j] = g; e16[j] = e;
+    gs += g; es += e;
+  }
+  s_scan[tid] = gs;
+  s_scan2[tid] = es;
+  __syncthreads();
+  unsigned eg = 0, ee = 0;
+  for (int t = 0; t < tid; ++t) { eg += s_scan[t]; ee += s_scan2[t]; }
+  int32_t *rp = a.out.rowptr + (size_t)h * (nb + 1);
+#pragma unroll
+  for (int j = 0; j < RP; ++j) {
+    const int R = RP * tid + j;
+    if (R < nb) {
+      if (pat == SA_BLOCK_CLUSTER) {
+        G->rowgt[R] = eg;
+        G->roweq[R] = ee;
+        rp[R] = (int)(eg + min(ee, need[4]) + (unsigned)R);  // R forced diagonals above this row
+      } else {
+        rp[R] = (int)eg;
+      }
+    }
+    eg += g16[j];
+    ee += e16[j];
+    if (R == nb - 1) rp[nb] = pat == SA_BLOCK_CLUSTER ? a.ksel[4] + nb : (int)eg;
+  }
+}
 
-  // ---- block CSR ---------------------------------------------------------------------------
+// ---- emission ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(BT) void idx_emit_kernel(IdxArgs a) {
+  const Shape &sh = a.sh;
+  const int p = blockIdx.x, h = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int N = sh.N, nb = sh.nb;
+  IdxScratch *G = a.scratch + h;
+  const int pat = G->pattern;
+  const int gw = p * WPB + wv;
+  const int gtid = p * BT + tid, gthreads = a.P * BT;
+  int32_t *cols = a.out.cols + (size_t)h * sh.k_v, *offs = a.out.offs + (size_t)h * sh.k_s;
   int32_t *rp = a.out.rowptr + (size_t)h * (nb + 1);
   int32_t *bc = a.out.blkcols + (size_t)h * sh.cap_b;
+  // columns and diagonals (Interval-Slash only)
+  const int kv = pat == SA_INTERVAL_SLASH ? a.ksel[2] : 0, ks = pat == SA_INTERVAL_SLASH ? a.ksel[3] : 0;
+  if (pat == SA_INTERVAL_SLASH) {
+    const int lo = min(gw * a.seg, N), hi = min(lo + a.seg, N);
+    for (int arr = 0; arr < 2; ++arr) {
+      const unsigned thr = G->thr[arr + 2], need = G->need[arr + 2];
+      unsigned grun = G->wgt[arr][gw], erun = G->weq[arr][gw];
+      int32_t *out = arr ? offs : cols;
+      if (a.ksel[arr + 2] > 0)
+        wave_visit4((arr ? a.s : a.v) + (size_t)h * N, lo, hi, true, [&](const Keys4 &v, int i0, int lim) {
+          emit_group(v, i0, lim, thr, need, grun, erun, [&](unsigned pos, int idx) { out[pos] = idx; });
+        });
+    }
+  }
+  for (int i = kv + gtid; i < sh.k_v; i += gthreads) cols[i] = -1;
+  for (int i = ks + gtid; i < sh.k_s; i += gthreads) offs[i] = -1;
+  if (gtid == 0) { a.out.n_cols[h] = kv; a.out.n_offs[h] = ks; }
+  // block CSR
   int total;
   if (pat == SA_BLOCK_CLUSTER) {
-    const long long ncand = (long long)nb * (nb - 1) / 2;
-    int k = sh.k_b - nb;
-    if (k < 0) k = 0;
-    if (k > ncand) k = (int)ncand;
-    // candidates: the entries C < R of the nb x nb map, one wave per row (coalesced reads)
-    const bool rowvec = (nb & 3) == 0;  // rows start 16-byte aligned
-    unsigned thr, need;
-    radix_select(
-        [&](auto fn) {
-          wave_rows_visit4(bb, nb, rowvec, [](int) {}, fn, [](int) {});
+    const unsigned thr = G->thr[4], need = G->need[4];
+    unsigned grun = 0, erun = 0;
+    wave_rows_visit4(
+        a.blk + (size_t)h * nb * nb, nb, gw, a.PW, (nb & 3) == 0,
+        [&](int R) { grun = G->rowgt[R]; erun = G->roweq[R]; },
+        [&](const Keys4 &v, int i0, int lim) {
+          // lim is the row index R: a selected entry lands after the R diagonals of the rows above
+          if (a.ksel[4] > 0)
+            emit_group(v, i0, lim, thr, need, grun, erun, [&](unsigned pos, int C) { bc[pos + lim] = C; });
         },
-        k, thr, need, sm);
-    // per-row counts (wave per row, coalesced), then a scan over rows
-    {
-      unsigned gt = 0, eq = 0;
-      wave_rows_visit4(
-          bb, nb, rowvec, [&](int) { gt = 0; eq = 0; },
-          [&](const Keys4 &v, int i0, int lim) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-              gt += i0 + j < lim && v.k[j] > thr;
-              eq += i0 + j < lim && v.k[j] == thr;
-            }
-          },
-          [&](int R) {
-            unsigned g2 = gt, e2 = eq;
-            for (int d = 32; d >= 1; d >>= 1) { g2 += __shfl_xor(g2, d); e2 += __shfl_xor(e2, d); }
-            if (lane == 0) { sm.rowgt[R] = g2; sm.roweq[R] = e2; }
-          });
-    }
-    __syncthreads();
-    // exclusive scan over rows: thread t owns rows 4t..4t+3 (nb <= 4096)
-    {
-      unsigned g4[4], e4[4], gs = 0, es = 0;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int R = 4 * tid + j;
-        g4[j] = R < nb ? sm.rowgt[R] : 0u;
-        e4[j] = R < nb ? sm.roweq[R] : 0u;
-        gs += g4[j];
-        es += e4[j];
-      }
-      unsigned eg, ee;
-      block_scan2(gs, es, eg, ee, sm);
-      __syncthreads();
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int R = 4 * tid + j;
-        if (R < nb) { sm.rowgt[R] = eg; sm.roweq[R] = ee; }
-        eg += g4[j];
-        ee += e4[j];
-      }
-    }
-    __syncthreads();
-    {
-      unsigned grun = 0, erun = 0;
-      wave_rows_visit4(
-          bb, nb, rowvec,
-          [&](int R) {
-            grun = sm.rowgt[R];
-            erun = sm.roweq[R];
-            if (lane == 0) rp[R] = (int)(grun + min(erun, need) + (unsigned)R);  // R forced diagonals above
-          },
-          [&](const Keys4 &v, int i0, int lim) {
-            // lim is the row index R: a selected entry lands after the R diagonals of the rows above
-            if (k > 0)
-              emit_group(v, i0, lim, thr, need, grun, erun,
-                         [&](unsigned pos, int C) { bc[pos + lim] = C; });
-          },
-          [&](int R) {
-            // the forced diagonal block closes the row
-            if (lane == 0) bc[grun + min(erun, need) + R] = R;
-          });
-    }
-    total = k + nb;
-    if (tid == 0) rp[nb] = total;
+        [&](int R) {
+          if (lane == 0) bc[grun + min(erun, need) + R] = R;  // the forced diagonal block closes the row
+        });
+    total = a.ksel[4] + nb;
   } else if (pat == SA_TRIANGULAR) {
-    // row R keeps C < min(sink, band start) and the band [max(R-L+1,0), R]
-    unsigned c4[4], cs = 0;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int R = 4 * tid + j;
+    for (int R = gtid; R < nb; R += gthreads) {
+      const int run = rp[R];
       const int bs = max(R - sh.local + 1, 0);
-      c4[j] = R < nb ? (unsigned)(min(sh.sink, bs) + (R - bs + 1)) : 0u;
-      cs += c4[j];
+      const int ns = min(sh.sink, bs);
+      for (int C = 0; C < ns; ++C) bc[run + C] = C;
+      for (int C = bs; C <= R; ++C) bc[run + ns + (C - bs)] = C;
     }
-    unsigned ex, dummy;
-    block_scan2(cs, 0u, ex, dummy, sm);
-    unsigned run = ex;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int R = 4 * tid + j;
-      if (R < nb) {
-        rp[R] = (int)run;
-        const int bs = max(R - sh.local + 1, 0);
-        const int ns = min(sh.sink, bs);
-        for (int C = 0; C < ns; ++C) bc[run + C] = C;
-        for (int C = bs; C <= R; ++C) bc[run + ns + (C - bs)] = C;
-        run += c4[j];
-        if (R == nb - 1) { rp[nb] = (int)run; sm.sel_remaining = run; }
-      }
-    }
-    __syncthreads();
-    total = (int)sm.sel_remaining;
+    total = rp[nb];
   } else {
-    for (int R = tid; R < nb; R += NT) { rp[R] = R; bc[R] = R; }
-    if (tid == 0) rp[nb] = nb;
+    for (int R = gtid; R < nb; R += gthreads) bc[R] = R;
     total = nb;
   }
-  for (int i = total + tid; i < sh.cap_b; i += NT) bc[i] = -1;
+  for (int i = total + gtid; i < sh.cap_b; i += gthreads) bc[i] = -1;
 }
 
 }  // namespace
 
-hipError_t launch_build_index(const Shape &sh, const Workspace &, sa_scores in, const Override &ov,
+size_t index_scratch_bytes(int n_heads) { return sizeof(IdxScratch) * (size_t)n_heads; }
+
+hipError_t launch_build_index(const Shape &sh, const Workspace &ws, sa_scores in, const Override &ov,
                               sa_index out, hipStream_t st) {
   IdxArgs a;
-  a.v = in.v; a.s = in.s; a.blk = in.blk;
+  a.v = (const unsigned *)in.v; a.s = (const unsigned *)in.s; a.blk = (const unsigned *)in.blk;
+  a.scratch = (IdxScratch *)ws.idx;
   a.sh = sh; a.ov = ov; a.out = out;
-  build_index_kernel<<<sh.Hq, NT, 0, st>>>(a);
+  int P = sh.N / 2048;
+  if (P < 1) P = 1;
+  if (P > kMaxParts) P = kMaxParts;
+  a.P = P; a.PW = P * WPB;
+  a.seg = ((sh.N + a.PW - 1) / a.PW + 255) / 256 * 256;
+  const long long ncand = (long long)sh.nb * (sh.nb - 1) / 2;
+  long long kb = (long long)sh.k_b - sh.nb;
+  if (kb < 0) kb = 0;
+  if (kb > ncand) kb = ncand;
+  a.ksel[0] = sh.probe_v < sh.N ? sh.probe_v : sh.N;
+  a.ksel[1] = sh.probe_s < sh.N ? sh.probe_s : sh.N;
+  a.ksel[2] = sh.k_v < sh.N ? sh.k_v : sh.N;
+  a.ksel[3] = sh.k_s < sh.N ? sh.k_s : sh.N;
+  a.ksel[4] = (int)kb;
+  const dim3 grid(P, sh.Hq);
+  idx_zero_kernel<<<sh.Hq, 256, 0, st>>>(a.scratch);
+  idx_hist_kernel<1><<<grid, BT, 0, st>>>(a);
+  idx_select_kernel<1><<<sh.Hq, BT, 0, st>>>(a);
+  idx_hist_kernel<2><<<grid, BT, 0, st>>>(a);
+  idx_select_kernel<2><<<sh.Hq, BT, 0, st>>>(a);
+  idx_hist_kernel<3><<<grid, BT, 0, st>>>(a);
+  idx_select_kernel<3><<<sh.Hq, BT, 0, st>>>(a);
+  idx_count_kernel<<<grid, BT, 0, st>>>(a);
+  idx_scan_kernel<<<sh.Hq, BT, 0, st>>>(a);
+  idx_emit_kernel<<<grid, BT, 0, st>>>(a);
   return hipGetLastError();
 }
 

@@ -32,8 +32,11 @@ struct Workspace {
   float2 *stats;                  // [Hq][64] (max * scale*log2e, 1/sum)
   uint32_t *offbits, *colbits;    // [Hq][N/32] membership bitmaps of offs / cols
   unsigned int *queue;            // [8] work-queue heads of the attention kernel
+  void *idx;                      // per-head scratch of the index builder
   uint16_t *kg, *vg;              // [Hq][roundup64(k_v)][128] gathered K / V rows of the selected columns
 };
+
+size_t index_scratch_bytes(int n_heads);
 
 hipError_t launch_estimate(const Shape &sh, const Workspace &ws, const uint16_t *Q,
                            const uint16_t *K, sa_scores out, hipStream_t st);
