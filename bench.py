@@ -152,6 +152,8 @@ def main():
     ap.add_argument("--also", default="cfg3", help="second workload reported under 'also' ('' to skip)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sample-rows", type=int, default=256)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 1 GiB device copy a few times (reference for HBM byte counters)")
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (heads shard without communication; "
@@ -160,6 +162,15 @@ def main():
     import torch
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if a.copy_calibration:
+        # a copy kernel of known size: reads 1 GiB, writes 1 GiB per launch
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").random_()
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"bytes_read": 1 << 30, "bytes_written": 1 << 30, "launches": 4}}))
+        return
     import paper_2412_06198_amd as sa
 
     sa.library()
