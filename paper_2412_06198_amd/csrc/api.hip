@@ -44,7 +44,7 @@ void carve(sa_ctx *c) {
   c->off[3] = o; o += align256((size_t)s.Hq * sa::kWin * 8);
   c->off[4] = o; o += align256((size_t)s.Hq * (s.N / 32) * 4);
   c->off[5] = o; o += align256((size_t)s.Hq * (s.N / 32) * 4);
-  const size_t kvg = (size_t)s.Hq * ((s.k_v + 63) / 64 * 64) * sa::kHeadDim * 2;
+  const size_t kvg = (size_t)s.Hq * ((s.k_v + 63) / 64 * 64) * (size_t)s.kv_rs * 2;
   c->off[6] = o; o += align256(kvg);
   c->off[7] = o; o += align256(kvg);
   c->off[8] = o; o += 256;

@@ -31,7 +31,7 @@ struct AttnArgs {
   uint16_t *O;
   const int32_t *n_cols, *cols, *n_offs, *offs, *rowptr, *blkcols;
   const uint32_t *offbits, *colbits;
-  uint16_t *Kg, *Vg;  // [Hq][kvg_rows][128] selected key columns, gathered once per call
+  uint16_t *Kg, *Vg;  // [Hq][kvg_rows][kv_rs] selected key columns, gathered once per call
   int kvg_rows;
   int Hq, Hkv, g, N, b, nb, nT, k_v, k_s, cap_b;
   int64_t q_hs, q_rs, kv_hs, kv_rs;
@@ -90,7 +90,7 @@ __global__ __launch_bounds__(256) void gather_columns_kernel(AttnArgs p) {
     int src = ci < nc ? p.cols[(size_t)h * p.k_v + ci] : 0;
     src = min(max(src, 0), p.N - 1);
     const size_t so = (size_t)kvh * p.kv_hs + (size_t)src * p.kv_rs + lcc * 8;
-    const size_t dofs = ((size_t)h * p.kvg_rows + ci) * kHeadDim + lcc * 8;
+    const size_t dofs = ((size_t)h * p.kvg_rows + ci) * p.kv_rs + lcc * 8;  // same row stride as K / V
     *(uint4 *)(p.Kg + dofs) = *(const uint4 *)(p.K + so);
     *(uint4 *)(p.Vg + dofs) = *(const uint4 *)(p.V + so);
   }
@@ -236,8 +236,8 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
   // ---- operands ------------------------------------------------------------------------------
   const uint16_t *__restrict__ Kh = p.K + (size_t)kvh * p.kv_hs;
   const uint16_t *__restrict__ Vh = p.V + (size_t)kvh * p.kv_hs;
-  const uint16_t *__restrict__ Kgh = p.Kg + (size_t)h * p.kvg_rows * kHeadDim;
-  const uint16_t *__restrict__ Vgh = p.Vg + (size_t)h * p.kvg_rows * kHeadDim;
+  const uint16_t *__restrict__ Kgh = p.Kg + (size_t)h * p.kvg_rows * p.kv_rs;
+  const uint16_t *__restrict__ Vgh = p.Vg + (size_t)h * p.kvg_rows * p.kv_rs;
   const uint32_t *__restrict__ offbm = p.offbits + (size_t)h * (N / 32);
   const uint32_t *__restrict__ colbm = p.colbits + (size_t)h * (N / 32);
 
@@ -255,35 +255,36 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
     for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
 
-  // ---- global -> register -> LDS pipeline ------------------------------------------------------
-  // this thread moves rows lrow+16n (n=0..3), 16-byte chunk lcc, of the K and the V tile
-  uint4 k0, k1, k2, k3, v0, v1, v2, v3;
-  const int lrow = tid >> 4, lcc = tid & 15;
-  const int kst = kswz(lrow, lcc), vst = vswz(lrow, lcc);  // rows +16n keep (row & 15), (row & 3)
-
-#define SA_ISSUE_LOADS(t)                                                                    \
-  {                                                                                          \
-    const uint16_t *kb, *vb;                                                                 \
-    size_t rs;                                                                               \
-    if ((t) < ntr) {                                                                         \
-      const int j0_ = __builtin_amdgcn_readfirstlane((int)tlist[t]) * BK;                    \
-      kb = Kh + (size_t)j0_ * p.kv_rs; vb = Vh + (size_t)j0_ * p.kv_rs; rs = (size_t)p.kv_rs; \
-    } else {                                                                                 \
-      const size_t g0_ = (size_t)((t) - ntr) * BK * kHeadDim;                                \
-      kb = Kgh + g0_; vb = Vgh + g0_; rs = kHeadDim;                                         \
-    }                                                                                        \
-    const size_t o_ = (size_t)lrow * rs + lcc * 8;                                           \
-    k0 = *(const uint4 *)(kb + o_); k1 = *(const uint4 *)(kb + o_ + 16 * rs);                \
-    k2 = *(const uint4 *)(kb + o_ + 32 * rs); k3 = *(const uint4 *)(kb + o_ + 48 * rs);      \
-    v0 = *(const uint4 *)(vb + o_); v1 = *(const uint4 *)(vb + o_ + 16 * rs);                \
-    v2 = *(const uint4 *)(vb + o_ + 32 * rs); v3 = *(const uint4 *)(vb + o_ + 48 * rs);      \
-  }
-#define SA_STORE_TILE(buf)                                                                   \
-  {                                                                                          \
-    *(uint4 *)&Ks[buf][kst] = k0; *(uint4 *)&Ks[buf][kst + 16 * 128] = k1;                   \
-    *(uint4 *)&Ks[buf][kst + 32 * 128] = k2; *(uint4 *)&Ks[buf][kst + 48 * 128] = k3;        \
-    *(uint4 *)&Vs[buf][vst] = v0; *(uint4 *)&Vs[buf][vst + 16 * 128] = v1;                   \
-    *(uint4 *)&Vs[buf][vst + 32 * 128] = v2; *(uint4 *)&Vs[buf][vst + 48 * 128] = v3;        \
+  // ---- global -> LDS pipeline -----------------------------------------------------------------
+  // K and V tiles go straight from global memory into LDS (global_load_lds_dwordx4: 16 bytes per
+  // lane, LDS address = M0 + 16*lane, so one instruction fills four 256-byte rows).  The XOR
+  // swizzle is applied on the global side: the lane that owns physical chunk pc of row r fetches
+  // logical chunk pc ^ swz(r).  Wave w moves rows 4w..4w+3 (+16n, n = 0..3) of both tiles.
+  const int rl = 4 * wv + (lane >> 4);  // (row & 15) of the rows this lane moves; (row & 3) = lane >> 4
+  const unsigned dmaK = (unsigned)(rl * (int)p.kv_rs * 2 + (((lane & 15) ^ rl) << 4));
+  const unsigned dmaV = (unsigned)(rl * (int)p.kv_rs * 2 + (((lane & 15) ^ ((lane >> 4) << 2)) << 4));
+  const unsigned ldsK0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) uint16_t *)&Ks[0][0] + 4 * wv * 256;
+  const unsigned ldsV0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) uint16_t *)&Vs[0][0] + 4 * wv * 256;
+  const size_t row16 = 16 * (size_t)p.kv_rs;  // elements between the rows of consecutive instructions
+#define SA_DMA16(gptr, voff, ldsb)                                                                    \
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(gptr), \
+               "s"(ldsb)                                                                              \
+               : "memory")
+#define SA_ISSUE_TILE(t, buf)                                                                    \
+  {                                                                                              \
+    const uint16_t *kb, *vb;                                                                     \
+    if ((t) < ntr) {                                                                             \
+      const size_t j0_ = (size_t)__builtin_amdgcn_readfirstlane((int)tlist[t]) * BK * p.kv_rs;    \
+      kb = Kh + j0_; vb = Vh + j0_;                                                              \
+    } else {                                                                                     \
+      const size_t g0_ = (size_t)((t) - ntr) * BK * p.kv_rs;                                     \
+      kb = Kgh + g0_; vb = Vgh + g0_;                                                            \
+    }                                                                                            \
+    const unsigned lk = ldsK0 + (buf) * (BK * 256), lv = ldsV0 + (buf) * (BK * 256);             \
+    SA_DMA16(kb, dmaK, lk); SA_DMA16(kb + row16, dmaK, lk + 16 * 256);                           \
+    SA_DMA16(kb + 2 * row16, dmaK, lk + 32 * 256); SA_DMA16(kb + 3 * row16, dmaK, lk + 48 * 256); \
+    SA_DMA16(vb, dmaV, lv); SA_DMA16(vb + row16, dmaV, lv + 16 * 256);                           \
+    SA_DMA16(vb + 2 * row16, dmaV, lv + 32 * 256); SA_DMA16(vb + 3 * row16, dmaV, lv + 48 * 256); \
   }
 
   // per-lane LDS byte offsets of the operand reads.  The swizzles only touch address bits 4..7,
@@ -306,18 +307,15 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
 #define SA_VTR(tile, db, key0) \
   __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)((const char *)(tile) + ((vbase ^ (unsigned)((db) << 6)) + (key0) * 256)))
 
-  if (ntot > 0) {
-    SA_ISSUE_LOADS(0);
-    SA_STORE_TILE(0);
-    if (ntot > 1) SA_ISSUE_LOADS(1);
-  }
+  if (ntot > 0) SA_ISSUE_TILE(0, 0);
 
   for (int t = 0; t < ntot; ++t) {
     const int cur = t & 1;
-    // tile t is complete in LDS[cur]; every wave has finished reading LDS[cur^1] (tile t-1)
+    // this wave's share of tile t has landed (nothing else is in flight); after the barrier the
+    // whole tile is in LDS[cur] and every wave has finished reading LDS[cur^1] (tile t-1)
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
     __syncthreads();
-    if (t + 1 < ntot) SA_STORE_TILE(cur ^ 1);
-    if (t + 2 < ntot) SA_ISSUE_LOADS(t + 2);
+    if (t + 1 < ntot) SA_ISSUE_TILE(t + 1, cur ^ 1);
 
     // ---- what this wave keeps of the tile: a 64-bit mask per lane over the key slots ---------
     // slot c (0..59 used) stands for key_local = c + 4*gg; see the accumulator layout below.
@@ -593,10 +591,10 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
   }  // work-queue loop
 }
 
-#undef SA_STORE_TILE
 #undef SA_KFRAG
 #undef SA_VTR
-#undef SA_ISSUE_LOADS
+#undef SA_ISSUE_TILE
+#undef SA_DMA16
 
 }  // namespace
 

@@ -33,7 +33,7 @@ struct Workspace {
   uint32_t *offbits, *colbits;    // [Hq][N/32] membership bitmaps of offs / cols
   unsigned int *queue;            // [8] work-queue heads of the attention kernel
   void *idx;                      // per-head scratch of the index builder
-  uint16_t *kg, *vg;              // [Hq][roundup64(k_v)][128] gathered K / V rows of the selected columns
+  uint16_t *kg, *vg;              // [Hq][roundup64(k_v)][kv_rs] gathered K / V rows of the selected columns
 };
 
 size_t index_scratch_bytes(int n_heads);
