@@ -358,14 +358,29 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
     const uint16_t *Kt = Ks[cur];
     f32x16 sacc[2];
 #pragma unroll
-    for (int hf = 0; hf < 2; ++hf) {
+    for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
       for (int r = 0; r < 16; ++r) sacc[hf][r] = 0.f;
+    {
+      // the 16 K fragments go through a ring of four registers: the LDS read of fragment i+4 is
+      // issued right after the MFMA that consumed fragment i, so reads stay 3-4 deep in flight
+      bf16x8 kf[4];
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 a = SA_KFRAG(Kt, hf, ks);
-        sacc[hf] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], sacc[hf], 0, 0, 0);
+      for (int i = 0; i < 4; ++i) kf[i] = SA_KFRAG(Kt, 0, i);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int hf = i >> 3, ks = i & 7;
+        sacc[hf] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i & 3], qf[ks], sacc[hf], 0, 0, 0);
+        if (i + 4 < 16) kf[i & 3] = SA_KFRAG(Kt, (i + 4) >> 3, (i + 4) & 7);
       }
+      // keep that order through instruction scheduling: 4 LDS reads, then MFMA / LDS read pairs
+      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+      for (int i = 0; i < 12; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
     }
     if (needmask) {
 #pragma unroll
@@ -409,22 +424,37 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
     l_run += psum;
     // ---- O^T += V^T P^T : k-slot (gg,e) of step (hf,u) <-> key 32hf + 16u + 8(e/4) + 4gg + e%4 ----
     const uint16_t *Vt = Vs[cur];
+    {
+      // 16 V^T fragments (4 key steps x 4 d blocks), each two transposing reads; same ring of four
+      s16x4 vlo[4], vhi[4];
 #pragma unroll
-    for (int hf = 0; hf < 2; ++hf)
+      for (int i = 0; i < 4; ++i) {
+        vlo[i] = SA_VTR(Vt, i & 3, 16 * (i >> 2));
+        vhi[i] = SA_VTR(Vt, i & 3, 16 * (i >> 2) + 8);
+      }
+      bf16x8 pb;
 #pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        bf16x8 pb;
+      for (int i = 0; i < 16; ++i) {
+        const int g = i >> 2, db = i & 3;  // key step g = 2*hf + u covers keys 16g .. 16g+15
+        if (db == 0) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) pb[e] = (__bf16)sacc[hf][8 * u + e];
-#pragma unroll
-        for (int db = 0; db < 4; ++db) {
-          const s16x4 lo = SA_VTR(Vt, db, 32 * hf + 16 * u);
-          const s16x4 hi = SA_VTR(Vt, db, 32 * hf + 16 * u + 8);
-          const s16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pb,
-                                                             oacc[db], 0, 0, 0);
+          for (int e = 0; e < 8; ++e) pb[e] = (__bf16)sacc[g >> 1][8 * (g & 1) + e];
+        }
+        const s16x8 av = __builtin_shufflevector(vlo[i & 3], vhi[i & 3], 0, 1, 2, 3, 4, 5, 6, 7);
+        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pb, oacc[db], 0, 0, 0);
+        if (i + 4 < 16) {
+          vlo[i & 3] = SA_VTR(Vt, (i + 4) & 3, 16 * ((i + 4) >> 2));
+          vhi[i & 3] = SA_VTR(Vt, (i + 4) & 3, 16 * ((i + 4) >> 2) + 8);
         }
       }
+      __builtin_amdgcn_sched_group_barrier(0x100, 8, 1);
+#pragma unroll
+      for (int i = 0; i < 12; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 4, 1);
+    }
   }
 
   // ---- selected diagonals: one 32-key tile per (wave, offset), no workgroup barriers -----------
