@@ -4,12 +4,15 @@
 //    rows only, then SumRows -> v and SumDiagonals -> s).  The softmax of a
 //    window row needs its maximum and normaliser over ALL keys before any
 //    column can be summed, so K is streamed twice:
-//      pass 1  S^T = K Qwin^T  (lane = query)  -> per-chunk (max, sum) partials
-//      pass 2  S   = Qwin K^T  (lane = key)    -> normalised weights, column sums,
-//                                                 diagonal sums through LDS
+//      pass 1  S^T = K Qwin^T  (lane = query)  -> per-chunk (max, sum) partials,
+//                                                 and the block sums of K on the way
+//      pass 2  S   = Qwin K^T  (lane = key)    -> normalised weights, column sums in
+//                                                 the lane, diagonal sums by lane shifts
 //    The 4 query heads of a GQA group ride on one K stream: wave w = head w.
+//    K tiles go global -> LDS directly (global_load_lds_dwordx4), double-buffered.
 //  * block map (Alg. 3 "Compute Blocked Representation"): fp32 block means of Q
-//    and K, an fp32 register-tiled GEMM for the block logits, a row softmax.
+//    and K, then one kernel that forms a 16-row strip of block logits with fp32
+//    MFMA, keeps it in registers, and writes its causal row softmax once.
 #include "sa_internal.h"
 
 namespace sa {
@@ -17,27 +20,25 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int KS = 136;  // LDS row stride (16-bit elements) of a K tile
+constexpr float kLog2e = 1.4426950408889634f;
 
 __device__ inline float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
 
-// ------------------------------------------------------------------ block means
-// grid (nb, Hq + Hkv), 256 threads: thread = (row group of 16, 16-byte column).
-__global__ __launch_bounds__(256) void block_mean_kernel(const uint16_t *Q, const uint16_t *K,
-                                                         Shape sh, float *qblk, float *kblk) {
+// ------------------------------------------------------------------ Q block means
+// grid (nb, Hq), 256 threads: thread = (row group of 16, 16-byte column).
+__global__ __launch_bounds__(256) void q_block_mean_kernel(const uint16_t *__restrict__ Q, Shape sh,
+                                                           float *__restrict__ qblk) {
   __shared__ float red[16][kHeadDim + 4];
-  const int R = blockIdx.x, hh = blockIdx.y, tid = threadIdx.x;
-  const bool isq = hh < sh.Hq;
-  const int64_t rs = isq ? sh.q_rs : sh.kv_rs;
-  const uint16_t *src = isq ? Q + (size_t)hh * sh.q_hs : K + (size_t)(hh - sh.Hq) * sh.kv_hs;
-  src += (size_t)R * sh.b * rs;
+  const int R = blockIdx.x, h = blockIdx.y, tid = threadIdx.x;
+  const uint16_t *src = Q + (size_t)h * sh.q_hs + (size_t)R * sh.b * sh.q_rs;
   const int cc = tid & 15, rg = tid >> 4;
   float acc[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) acc[e] = 0.f;
   for (int r = rg; r < sh.b; r += 16) {
-    const uint4 x = *(const uint4 *)(src + (size_t)r * rs + cc * 8);
+    const uint4 x = *(const uint4 *)(src + (size_t)r * sh.q_rs + cc * 8);
     const uint32_t wds[4] = {x.x, x.y, x.z, x.w};
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -52,9 +53,7 @@ __global__ __launch_bounds__(256) void block_mean_kernel(const uint16_t *Q, cons
     float sum = 0.f;
 #pragma unroll
     for (int r = 0; r < 16; ++r) sum += red[r][tid];
-    float *dst = isq ? qblk + ((size_t)hh * sh.nb + R) * kHeadDim
-                     : kblk + ((size_t)(hh - sh.Hq) * sh.nb + R) * kHeadDim;
-    dst[tid] = sum * (1.0f / (float)sh.b);
+    qblk[((size_t)h * sh.nb + R) * kHeadDim + tid] = sum * (1.0f / (float)sh.b);
   }
 }
 
@@ -62,7 +61,7 @@ __global__ __launch_bounds__(256) void block_mean_kernel(const uint16_t *Q, cons
 // Q window fragments of one head: lane (q = lane%32, gg = lane/32) holds window row
 // 32*qh + q, elements d = 16*ks + 8*gg .. +7.  The same registers serve as the B operand
 // of K Q^T (pass 1) and as the A operand of Q K^T (pass 2).
-__device__ inline void load_qwin(const uint16_t *Q, const Shape &sh, int hq, int lane,
+__device__ inline void load_qwin(const uint16_t *__restrict__ Q, const Shape &sh, int hq, int lane,
                                  bf16x8 (&qf)[2][8]) {
   const int q = lane & 31, gg = lane >> 5;
 #pragma unroll
@@ -75,24 +74,51 @@ __device__ inline void load_qwin(const uint16_t *Q, const Shape &sh, int hq, int
   }
 }
 
-// 64 keys x 128 d of K into LDS (rows past N are clamped; callers mask them).
-__device__ inline void stage_k_tile(const uint16_t *Kh, const Shape &sh, int j0, int tid,
-                                    uint16_t *Ks) {
-  const int lrow = tid >> 4, lcc = tid & 15;
-#pragma unroll
-  for (int n = 0; n < 4; ++n) {
-    const int row = lrow + 16 * n;
-    const int src = min(j0 + row, sh.N - 1);
-    *(uint4 *)&Ks[row * KS + lcc * 8] = *(const uint4 *)(Kh + (size_t)src * sh.kv_rs + lcc * 8);
+// A K tile is 64 keys x 256 B in LDS, the 16-byte chunks of a row XOR-swizzled with the row
+// number (chunk c of row r sits at chunk c ^ (r & 15)): the b128 fragment reads of 32 rows are
+// conflict-free without padding.  The swizzle is applied on the global side of the copy: the
+// lane that owns physical chunk pc of row r fetches logical chunk pc ^ (r & 15).  One
+// instruction moves four rows (16 bytes per lane, LDS address = M0 + 16*lane); wave w moves rows
+// 4w..4w+3 (+16n, n = 0..3).
+#define SA_DMA16(gptr, voff, ldsb)                                                                    \
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(gptr), \
+               "s"(ldsb)                                                                              \
+               : "memory")
+
+struct KTileCopy {
+  unsigned voff;   // per-lane byte offset inside a 16-row slab of K
+  unsigned lds0;   // LDS byte address of this wave's first row in buffer 0
+  size_t row16;    // elements between the rows of consecutive instructions
+  __device__ inline void init(const uint16_t *ks0, int wv, int lane, int64_t kv_rs) {
+    const int rl = 4 * wv + (lane >> 4);
+    voff = (unsigned)(rl * (int)kv_rs * 2 + (((lane & 15) ^ rl) << 4));
+    lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) const uint16_t *)ks0 + 4 * wv * 256;
+    row16 = 16 * (size_t)kv_rs;
   }
+  __device__ inline void issue(const uint16_t *kb, int buf) const {
+    const unsigned l = lds0 + buf * (64 * 256);
+    SA_DMA16(kb, voff, l);
+    SA_DMA16(kb + row16, voff, l + 16 * 256);
+    SA_DMA16(kb + 2 * row16, voff, l + 32 * 256);
+    SA_DMA16(kb + 3 * row16, voff, l + 48 * 256);
+  }
+};
+
+// fragment (rows 32*kh + q, logical chunk 2*ks + gg) of a swizzled tile
+__device__ inline bf16x8 k_frag(const uint16_t *tile, unsigned kbase, int gg, int kh, int ks) {
+  return *(const bf16x8 *)((const char *)tile + ((kbase ^ (unsigned)((2 * ks + gg) << 4)) + kh * 32 * 256));
 }
 
 // pass 1: grid (nchunks, Hkv, ceil(g/4)), 256 threads.
-__global__ __launch_bounds__(256) void window_stats_kernel(const uint16_t *Q, const uint16_t *K,
-                                                           Shape sh, float c, float2 *part,
-                                                           float *s_out) {
-  __shared__ __attribute__((aligned(16))) uint16_t Ks[64 * KS];
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+__global__ __launch_bounds__(256) void window_stats_kernel(const uint16_t *__restrict__ Q,
+                                                           const uint16_t *__restrict__ K, Shape sh,
+                                                           float c, float2 *__restrict__ part,
+                                                           float *__restrict__ s_out,
+                                                           float *__restrict__ kblk) {
+  __shared__ __attribute__((aligned(16))) uint16_t Ks[2][64 * 128];
+  __shared__ float ksum[2][4][kHeadDim];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int q = lane & 31, gg = lane >> 5;
   const int chunk = blockIdx.x, kvh = blockIdx.y;
   const int hsub = 4 * blockIdx.z + wv;
@@ -100,7 +126,13 @@ __global__ __launch_bounds__(256) void window_stats_kernel(const uint16_t *Q, co
   const int hq = kvh * sh.g + (head_ok ? hsub : 0);
   const int jc0 = chunk * kChunk;
   const int jc1 = min(jc0 + kChunk, sh.N);
-  const uint16_t *Kh = K + (size_t)kvh * sh.kv_hs;
+  const int nt = (jc1 - jc0) >> 6;  // N is a multiple of 64: whole tiles only
+  const uint16_t *Kh = K + (size_t)kvh * sh.kv_hs + (size_t)jc0 * sh.kv_rs;
+  const bool do_means = blockIdx.z == 0;
+
+  KTileCopy cp;
+  cp.init(&Ks[0][0], wv, lane, sh.kv_rs);
+  cp.issue(Kh, 0);
 
   // the slash scores are accumulated with atomics in pass 2: clear this chunk's share now
   if (head_ok)
@@ -109,11 +141,45 @@ __global__ __launch_bounds__(256) void window_stats_kernel(const uint16_t *Q, co
   bf16x8 qf[2][8];
   load_qwin(Q, sh, hq, lane, qf);
   float m[2] = {-INFINITY, -INFINITY}, z[2] = {0.f, 0.f};
+  const unsigned kbase = (unsigned)(q * 256) | (unsigned)((q & 15) << 4);
 
-  for (int j0 = jc0; j0 < jc1; j0 += 64) {
+  // block sums of K: thread = (dword column cd of the 256-byte rows, rows 16*wv .. 16*wv+15)
+  const int cd = tid & 63;
+  const int tpb = sh.b >> 6;  // tiles per block: 1 or 2
+  float ks_lo = 0.f, ks_hi = 0.f;
+  int pending = -1;           // block whose four partial sums wait in ksum[pending & 1]
+
+  for (int t = 0; t < nt; ++t) {
+    const int cur = t & 1;
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of tile t has landed
     __syncthreads();
-    stage_k_tile(Kh, sh, j0, tid, Ks);
-    __syncthreads();
+    if (t + 1 < nt) cp.issue(Kh + (size_t)(t + 1) * 64 * sh.kv_rs, cur ^ 1);
+    const uint16_t *Kt = Ks[cur];
+    const int j0 = jc0 + 64 * t;
+
+    if (do_means) {
+      if (pending >= 0 && tid < kHeadDim) {
+        const float(*ps)[kHeadDim] = ksum[pending & 1];
+        kblk[((size_t)kvh * sh.nb + pending) * kHeadDim + tid] =
+            ((ps[0][tid] + ps[1][tid]) + (ps[2][tid] + ps[3][tid])) * (1.0f / (float)sh.b);
+      }
+      pending = -1;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = 16 * wv + r;
+        const uint32_t x = *(const uint32_t *)((const char *)Kt + row * 256 +
+                                               ((((cd >> 2) ^ r) << 4) | ((cd & 3) << 2)));
+        ks_lo += bf16_bits_to_f32(x & 0xFFFFu);
+        ks_hi += bf16_bits_to_f32(x >> 16);
+      }
+      if ((t + 1) % tpb == 0) {
+        const int C = j0 / sh.b;
+        *(float2 *)&ksum[C & 1][wv][2 * cd] = make_float2(ks_lo, ks_hi);
+        ks_lo = 0.f; ks_hi = 0.f;
+        pending = C;
+      }
+    }
+
     f32x16 acc[2][2];  // [key half][query half]
 #pragma unroll
     for (int kh = 0; kh < 2; ++kh) {
@@ -123,38 +189,53 @@ __global__ __launch_bounds__(256) void window_stats_kernel(const uint16_t *Q, co
         for (int r = 0; r < 16; ++r) acc[kh][qh][r] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 a = *(const bf16x8 *)&Ks[(32 * kh + q) * KS + 16 * ks + 8 * gg];
+        const bf16x8 a = k_frag(Kt, kbase, gg, kh, ks);
 #pragma unroll
         for (int qh = 0; qh < 2; ++qh)
           acc[kh][qh] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qh][ks], acc[kh][qh], 0, 0, 0);
       }
     }
     // lane = query 32qh+q ; acc[kh][qh][r] <-> key j0 + 32kh + 8(r/4) + 4gg + r%4
-    const bool tail = j0 + 63 > sh.N - sh.w;  // causal / end-of-sequence masking only near the end
+    const bool tail = j0 + 63 > sh.N - sh.w;  // causal masking only in the last tile of the sequence
 #pragma unroll
     for (int qh = 0; qh < 2; ++qh) {
-      const int jmax = sh.N - sh.w + 32 * qh + q;  // last visible key of this window row
       float tmax = -INFINITY;
+      if (tail) {
+        const int jmax = sh.N - sh.w + 32 * qh + q;  // last visible key of this window row
 #pragma unroll
-      for (int kh = 0; kh < 2; ++kh)
+        for (int kh = 0; kh < 2; ++kh)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          if (tail) {
+          for (int r = 0; r < 16; ++r) {
             const int j = j0 + 32 * kh + 8 * (r / 4) + 4 * gg + (r % 4);
             if (j > jmax) acc[kh][qh][r] = -INFINITY;
           }
-          tmax = fmaxf(tmax, acc[kh][qh][r]);
-        }
+      }
+#pragma unroll
+      for (int kh = 0; kh < 2; ++kh)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, acc[kh][qh][r]);
+      // the reference moves only when a row's maximum grew by more than 2^8 (terms stay <= 256)
       const float m_new = fmaxf(m[qh], tmax * c);
-      const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+      if (__any(m_new - m[qh] > 8.f)) {
+        z[qh] *= __builtin_amdgcn_exp2f(m[qh] - ((m_new == -INFINITY) ? 0.f : m_new));
+        m[qh] = m_new;
+      }
+      const float m_ref = (m[qh] == -INFINITY) ? 0.f : m[qh];
       float sum = 0.f;
 #pragma unroll
       for (int kh = 0; kh < 2; ++kh)
 #pragma unroll
         for (int r = 0; r < 16; ++r)
-          sum += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[kh][qh][r], c, -m_safe));
-      z[qh] = z[qh] * __builtin_amdgcn_exp2f(m[qh] - m_safe) + sum;
-      m[qh] = m_new;
+          sum += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[kh][qh][r], c, -m_ref));
+      z[qh] += sum;
+    }
+  }
+  if (do_means) {
+    __syncthreads();
+    if (pending >= 0 && tid < kHeadDim) {
+      const float(*ps)[kHeadDim] = ksum[pending & 1];
+      kblk[((size_t)kvh * sh.nb + pending) * kHeadDim + tid] =
+          ((ps[0][tid] + ps[1][tid]) + (ps[2][tid] + ps[3][tid])) * (1.0f / (float)sh.b);
     }
   }
 #pragma unroll
@@ -162,221 +243,315 @@ __global__ __launch_bounds__(256) void window_stats_kernel(const uint16_t *Q, co
     const float mp = __shfl_xor(m[qh], 32), zp = __shfl_xor(z[qh], 32);
     const float M = fmaxf(m[qh], mp);
     float Z = 0.f;
-    if (M != -INFINITY) Z = z[qh] * __builtin_amdgcn_exp2f(m[qh] - M) + zp * __builtin_amdgcn_exp2f(mp - M);
+    if (M != -INFINITY) {
+      if (m[qh] != -INFINITY) Z += z[qh] * __builtin_amdgcn_exp2f(m[qh] - M);
+      if (mp != -INFINITY) Z += zp * __builtin_amdgcn_exp2f(mp - M);
+    }
     const int i = 32 * qh + q;
     if (head_ok && gg == 0 && i < sh.w)
       part[((size_t)hq * sh.nchunks + chunk) * kWin + i] = make_float2(M, Z);
   }
 }
 
-// combine the per-chunk partials: grid Hq, 1024 threads = 16 chunk slices x 64 window rows.
-__global__ __launch_bounds__(1024) void window_stats_reduce_kernel(const float2 *part, int nchunks,
-                                                                  int w, float2 *stats) {
-  __shared__ float2 red[16][kWin];
+// combine the per-chunk partials into bias[i] = max_i + log2(sum_i) (log2 domain), so that a
+// window weight is exp2(logit * scale * log2e - bias).  Rows past the window get +inf (weight 0).
+// grid Hq, 1024 threads = 16 chunk slices x 64 window rows.
+__global__ __launch_bounds__(1024) void window_stats_reduce_kernel(const float2 *__restrict__ part,
+                                                                  int nchunks, int w,
+                                                                  float *__restrict__ bias) {
+  __shared__ float redm[16][kWin];
+  __shared__ float redz[16][kWin];
   const int hq = blockIdx.x, i = threadIdx.x & 63, sl = threadIdx.x >> 6;
   const float2 *p = part + (size_t)hq * nchunks * kWin + i;
-  float M = -INFINITY, Z = 0.f;
+  float M = -INFINITY;
+  if (i < w)
+    for (int cidx = sl; cidx < nchunks; cidx += 16) M = fmaxf(M, p[(size_t)cidx * kWin].x);
+  redm[sl][i] = M;
+  __syncthreads();
+  float Mt = -INFINITY;
+#pragma unroll
+  for (int k = 0; k < 16; ++k) Mt = fmaxf(Mt, redm[k][i]);
+  float Z = 0.f;
   if (i < w)
     for (int cidx = sl; cidx < nchunks; cidx += 16) {
       const float2 e = p[(size_t)cidx * kWin];
-      if (e.x == -INFINITY) continue;
-      const float Mn = fmaxf(M, e.x);
-      Z = Z * __builtin_amdgcn_exp2f(M - Mn) + e.y * __builtin_amdgcn_exp2f(e.x - Mn);
-      M = Mn;
+      if (e.x != -INFINITY) Z += e.y * __builtin_amdgcn_exp2f(e.x - Mt);
     }
-  red[sl][i] = make_float2(M, Z);
+  redz[sl][i] = Z;
   __syncthreads();
   if (sl == 0) {
-    if (i >= w) { stats[(size_t)hq * kWin + i] = make_float2(INFINITY, 0.f); return; }
-    float Mt = -INFINITY;
-    for (int k = 0; k < 16; ++k) Mt = fmaxf(Mt, red[k][i].x);
     float Zt = 0.f;
-    for (int k = 0; k < 16; ++k)
-      if (red[k][i].x != -INFINITY) Zt += red[k][i].y * __builtin_amdgcn_exp2f(red[k][i].x - Mt);
-    stats[(size_t)hq * kWin + i] = make_float2(Mt, 1.0f / Zt);
+#pragma unroll
+    for (int k = 0; k < 16; ++k) Zt += redz[k][i];
+    bias[(size_t)hq * kWin + i] = i < w ? Mt + __builtin_amdgcn_logf(Zt) : INFINITY;  // v_log_f32 = log2
   }
 }
 
-// pass 2: grid (nchunks, Hkv, ceil(g/4)), 256 threads.
-__global__ __launch_bounds__(256) void window_scores_kernel(const uint16_t *Q, const uint16_t *K,
-                                                            Shape sh, float c, const float2 *stats,
-                                                            float *v_out, float *s_out) {
-  __shared__ __attribute__((aligned(16))) uint16_t Ks[64 * KS];
-  __shared__ float sdiag[4][kChunk + kWin];
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+// Lane shifts of a whole wavefront (DPP wave_shl:1 / wave_shr:1): lane l takes lane l+1 (l-1);
+// the lane without a source gets 0.
+__device__ inline float wave_shl1(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x130, 0xF, 0xF, true));
+}
+__device__ inline float wave_shr1(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x138, 0xF, 0xF, true));
+}
+
+// Weights of one 64-key tile (pass 2).  After the MFMAs lane l holds key 32kh + l%32 and
+// register r of acc[kh][qh] window row 32qh + 8(r/4) + 4(l/32) + r%4.  v_permlane32_swap of
+// the two key halves turns that into "register = one window row, lane = key 0..63": the row
+// constants are wave-uniform and the column sum stays in the lane.
+//
+// Diagonal sums without LDS: the rows are taken in DESCENDING order, step tau = 64*tile + 63 - i,
+// so that the offset of element (i, lane l) is A - (tau + l) for a chunk constant A.  `run`
+// shifts one lane down per step (run[l] <- run[l+1] + weight): a slot then collects exactly one
+// offset over 64 consecutive steps, is complete when it reaches lane 0, and `done` picks it up
+// there while shifting the other way, so that after the 64 rows of a tile done[l] is the finished
+// sum of offset (N - w - j0) + l.  Sums that straddle a chunk boundary are the only partial ones.
+template <bool TAIL>
+__device__ inline float scores_tile(const f32x16 (&acc)[2][2], const float (&bias)[kWin], float c,
+                                    int lim0, bool lane0, float &run, float &done) {
+  float colsum = 0.f;
+#pragma unroll
+  for (int qh = 1; qh >= 0; --qh)
+#pragma unroll
+    for (int rq = 3; rq >= 0; --rq) {
+      float x[2][4];
+#pragma unroll
+      for (int rm = 0; rm < 4; ++rm) {
+        const auto pr = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[0][qh][4 * rq + rm]),
+                                                         __float_as_uint(acc[1][qh][4 * rq + rm]), false, false);
+        x[0][rm] = __uint_as_float(pr[0]);
+        x[1][rm] = __uint_as_float(pr[1]);
+      }
+#pragma unroll
+      for (int u = 1; u >= 0; --u)
+#pragma unroll
+        for (int rm = 3; rm >= 0; --rm) {
+          const int i = 32 * qh + 8 * rq + 4 * u + rm;
+          float e = __builtin_amdgcn_exp2f(__builtin_fmaf(x[u][rm], c, -bias[i]));
+          if (TAIL) e = (lim0 + i >= 0) ? e : 0.f;  // key j0 + lane visible to row i iff j <= N-w+i
+          colsum += e;
+          run = wave_shl1(run) + e;
+          const float up = wave_shr1(done);  // a cross-lane move: never under a lane condition
+          done = lane0 ? run : up;
+        }
+    }
+  return colsum;
+}
+
+// pass 2: grid (nchunks, Hkv, ceil(g/4)), 256 threads.  Chunks are walked in the reverse order
+// of pass 1, so that the most recently streamed part of K is re-read first.
+__global__ __launch_bounds__(256) void window_scores_kernel(const uint16_t *__restrict__ Q,
+                                                            const uint16_t *__restrict__ K, Shape sh,
+                                                            float c, const float *__restrict__ bias_g,
+                                                            float *__restrict__ v_out,
+                                                            float *__restrict__ s_out) {
+  __shared__ __attribute__((aligned(16))) uint16_t Ks[2][64 * 128];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int q = lane & 31, gg = lane >> 5;
-  const int chunk = blockIdx.x, kvh = blockIdx.y;
+  const int chunk = sh.nchunks - 1 - (int)blockIdx.x, kvh = sh.Hkv - 1 - (int)blockIdx.y;
   const int hsub = 4 * blockIdx.z + wv;
   const bool head_ok = hsub < sh.g;
   const int hq = kvh * sh.g + (head_ok ? hsub : 0);
   const int jc0 = chunk * kChunk;
   const int jc1 = min(jc0 + kChunk, sh.N);
-  const uint16_t *Kh = K + (size_t)kvh * sh.kv_hs;
+  const int nt = (jc1 - jc0) >> 6;
+  const uint16_t *Kh = K + (size_t)kvh * sh.kv_hs + (size_t)jc0 * sh.kv_rs;
 
-  for (int i = lane; i < kChunk + kWin; i += 64) sdiag[wv][i] = 0.f;
+  KTileCopy cp;
+  cp.init(&Ks[0][0], wv, lane, sh.kv_rs);
+  cp.issue(Kh, 0);
 
   bf16x8 qf[2][8];
   load_qwin(Q, sh, hq, lane, qf);
-  // this lane's window rows: i(qh,r) = 32qh + 8(r/4) + 4gg + r%4
-  float mrow[2][16], zinv[2][16];
+  float bias[kWin];  // wave-uniform: lives in scalar registers
 #pragma unroll
-  for (int qh = 0; qh < 2; ++qh)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int i = 32 * qh + 8 * (r / 4) + 4 * gg + (r % 4);
-      const float2 st = stats[(size_t)hq * kWin + i];
-      mrow[qh][r] = st.x;
-      zinv[qh][r] = i < sh.w ? st.y : 0.f;  // rows past the window contribute nothing
-    }
+  for (int i = 0; i < kWin; ++i)
+    bias[i] = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(bias_g[(size_t)hq * kWin + i])));
+  const unsigned kbase = (unsigned)(q * 256) | (unsigned)((q & 15) << 4);
+  float *srow = s_out + (size_t)hq * sh.N;
+  float run = 0.f, done = 0.f;
+  float cv = c;  // in a vector register: an FMA takes only one scalar operand, and that is the row's bias
+  asm volatile("" : "+v"(cv));
 
-  for (int j0 = jc0; j0 < jc1; j0 += 64) {
+  for (int t = 0; t < nt; ++t) {
+    const int cur = t & 1;
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
     __syncthreads();
-    stage_k_tile(Kh, sh, j0, tid, Ks);
-    __syncthreads();
+    if (t + 1 < nt) cp.issue(Kh + (size_t)(t + 1) * 64 * sh.kv_rs, cur ^ 1);
+    const uint16_t *Kt = Ks[cur];
+    const int j0 = jc0 + 64 * t;
+
+    f32x16 acc[2][2];  // [key half][query half]
 #pragma unroll
     for (int kh = 0; kh < 2; ++kh) {
-      f32x16 acc[2];
 #pragma unroll
       for (int qh = 0; qh < 2; ++qh)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[qh][r] = 0.f;
+        for (int r = 0; r < 16; ++r) acc[kh][qh][r] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 kf = *(const bf16x8 *)&Ks[(32 * kh + q) * KS + 16 * ks + 8 * gg];
+        const bf16x8 kf = k_frag(Kt, kbase, gg, kh, ks);
 #pragma unroll
         for (int qh = 0; qh < 2; ++qh)
-          acc[qh] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[qh][ks], kf, acc[qh], 0, 0, 0);
+          acc[kh][qh] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[qh][ks], kf, acc[kh][qh], 0, 0, 0);
       }
-      // lane = key j ; acc[qh][r] <-> window row i(qh,r)
-      const int j = j0 + 32 * kh + q;
-      float colsum = 0.f;
-#pragma unroll
-      for (int qh = 0; qh < 2; ++qh)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int i = 32 * qh + 8 * (r / 4) + 4 * gg + (r % 4);
-          float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[qh][r], c, -mrow[qh][r])) * zinv[qh][r];
-          if (j > sh.N - sh.w + i || j >= sh.N) pe = 0.f;
-          colsum += pe;
-          // diagonal offset o = (N-w+i) - j ; slot = o - (N-w - (jc0+kChunk-1)) = i + jc0+kChunk-1 - j.
-          // Lanes (q,0) and (q+4,1) hold the same offset: fold the partner in first, so that
-          // every lane that writes owns its slot and the summation order is fixed.
-          const float partner = __shfl(pe, 32 + ((q + 4) & 31));
-          const int slot = i + (jc0 + kChunk - 1 - j);
-          if (gg == 0) sdiag[wv][slot] += (q < 28) ? pe + partner : pe;
-          else if (q < 4) sdiag[wv][slot] += pe;
-        }
-      colsum += __shfl_xor(colsum, 32);
-      if (head_ok && gg == 0 && j < sh.N) v_out[(size_t)hq * sh.N + j] = colsum;
+    }
+    float colsum;
+    if (j0 + 63 > sh.N - sh.w)
+      colsum = scores_tile<true>(acc, bias, cv, sh.N - sh.w - j0 - lane, lane == 0, run, done);
+    else
+      colsum = scores_tile<false>(acc, bias, cv, 0, lane == 0, run, done);
+    if (head_ok) {
+      v_out[(size_t)hq * sh.N + j0 + lane] = colsum;
+      // The first tile's sums lack the previous chunk's rows (all but lane 0): they are added to
+      // the zeroed slot, as is that chunk's remainder below.  Every offset so receives at most
+      // two partial sums, so the result does not depend on the order of the atomics.
+      const int o = sh.N - sh.w - j0 + lane;
+      if (o < sh.N) {
+        if (t == 0) atomicAdd(&srow[o], done);
+        else srow[o] = done;
+      }
     }
   }
-  // every offset receives at most two partial sums (this chunk and one neighbour), so the
-  // floating-point result does not depend on the order of the atomics
-  if (head_ok) {
-    const int obase = sh.N - sh.w - (jc0 + kChunk - 1);
-    for (int i = lane; i < kChunk + kWin; i += 64) {
-      const int o = obase + i;
-      const float val = sdiag[wv][i];
-      if (o >= 0 && o < sh.N && val != 0.f) atomicAdd(&s_out[(size_t)hq * sh.N + o], val);
-    }
+  // what is left in `run` belongs to the next chunk's first tile: lane l holds offset
+  // (N - w - jc1) + 64 - l, l = 1..63
+  if (head_ok && lane > 0) {
+    const int o = sh.N - sh.w - jc1 + 64 - lane;
+    if (o >= 0 && o < sh.N) atomicAdd(&srow[o], run);
   }
 }
 
 // ------------------------------------------------------------------ block map
-// raw block logits scale * Qblk[R].Kblk[C] for the tiles on or below the diagonal.
-// grid (nb/64 rounded up, nb/64 rounded up, Hq), 256 threads, 4x4 outputs per thread.
-__global__ __launch_bounds__(256) void block_logits_kernel(const float *qblk, const float *kblk,
-                                                           Shape sh, float *blk) {
-  __shared__ __attribute__((aligned(16))) float Qt[64][68];  // [k][row]
-  __shared__ __attribute__((aligned(16))) float Kt[64][68];  // [k][col]
-  const int tc = blockIdx.x, tr = blockIdx.y, h = blockIdx.z;
-  if (tc > tr) return;
-  const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
+// blk[h][R][C] = softmax over C <= R of scale * Qblk[R].Kblk[C]; entries C > R are 0.
+// One workgroup = 16 rows of one head.  v_mfma_f32_16x16x4_f32 forms 16x16 logit tiles
+// (lane l: column l%16, rows 4(l/16) + r); the column tiles of the strip go round-robin to the
+// four waves and stay in registers (MT tiles per wave) until the row maxima and sums are known,
+// so blk is written exactly once.  The contraction index is split so that MFMA step (e, x) of
+// lane group g = l/16 takes element 16e + 4g + x of a row: one load instruction then reads 64
+// contiguous bytes of each of the 16 rows.
+// grid (ceil(nb/16), Hq), 256 threads; strips are taken longest first.
+template <int MT>
+__global__ __launch_bounds__(256) void block_map_kernel(const float *__restrict__ qblk,
+                                                        const float *__restrict__ kblk, Shape sh,
+                                                        float c2, float *__restrict__ blk) {
+  __shared__ float red[2][4][16];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n = lane & 15, g = lane >> 4;
   const int nb = sh.nb;
+  const int strip = (int)gridDim.x - 1 - (int)blockIdx.x, h = blockIdx.y;
+  const int R0 = 16 * strip;
+  const int T = strip + 1;  // column tiles 0..strip hold every C <= R of this strip
   const float *qsrc = qblk + (size_t)h * nb * kHeadDim;
   const float *ksrc = kblk + (size_t)(h / sh.g) * nb * kHeadDim;
-  float acc[4][4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
-  for (int k0 = 0; k0 < kHeadDim; k0 += 64) {
-    __syncthreads();
-    // 64 rows x 64 k = 1024 float4 per matrix; thread moves 4 of each
-#pragma unroll
-    for (int n = 0; n < 4; ++n) {
-      const int idx = tid + 256 * n;
-      const int row = idx >> 4, kq = (idx & 15) * 4;
-      const int R = min(tr * 64 + row, nb - 1), C = min(tc * 64 + row, nb - 1);
-      const float4 a = *(const float4 *)(qsrc + (size_t)R * kHeadDim + k0 + kq);
-      const float4 b = *(const float4 *)(ksrc + (size_t)C * kHeadDim + k0 + kq);
-      Qt[kq + 0][row] = a.x; Qt[kq + 1][row] = a.y; Qt[kq + 2][row] = a.z; Qt[kq + 3][row] = a.w;
-      Kt[kq + 0][row] = b.x; Kt[kq + 1][row] = b.y; Kt[kq + 2][row] = b.z; Kt[kq + 3][row] = b.w;
-    }
-    __syncthreads();
-#pragma unroll 8
-    for (int k = 0; k < 64; ++k) {
-      const float4 a = *(const float4 *)&Qt[k][ty * 4];
-      const float4 b = *(const float4 *)&Kt[k][tx * 4];
-      const float av[4] = {a.x, a.y, a.z, a.w}, bv[4] = {b.x, b.y, b.z, b.w};
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_fmaf(av[i], bv[j], acc[i][j]);
-    }
-  }
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int R = tr * 64 + ty * 4 + i;
-    if (R >= nb) continue;
-    const int C = tc * 64 + tx * 4;
-    float *dst = blk + ((size_t)h * nb + R) * nb + C;
-    if ((nb & 3) == 0 && C + 3 < nb) {
-      *(float4 *)dst = make_float4(acc[i][0] * sh.scale, acc[i][1] * sh.scale, acc[i][2] * sh.scale,
-                                   acc[i][3] * sh.scale);
-    } else {
-      for (int j = 0; j < 4 && C + j < nb; ++j) dst[j] = acc[i][j] * sh.scale;
-    }
-  }
-}
 
-// in-place causal row softmax of the block logits; entries C > R become 0.
-// grid (nb, Hq), 256 threads; rows hold at most kMaxSeq/64 = 4096 blocks.
-__global__ __launch_bounds__(256) void block_softmax_kernel(Shape sh, float *blk) {
-  __shared__ float red[4];
-  const int R = blockIdx.x, h = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  const int nb = sh.nb;
-  float *row = blk + ((size_t)h * nb + R) * nb;
-  constexpr int PER = 16;
-  constexpr float LOG2E = 1.4426950408889634f;
-  float x[PER];
-  float mx = -INFINITY;
+  float4 a4[8];
+  {
+    const float *ap = qsrc + (size_t)min(R0 + n, nb - 1) * kHeadDim + 4 * g;
 #pragma unroll
-  for (int n = 0; n < PER; ++n) {
-    const int C = tid + 256 * n;
-    x[n] = (C <= R && C < nb) ? row[C] * LOG2E : -INFINITY;
-    mx = fmaxf(mx, x[n]);
+    for (int e = 0; e < 8; ++e) a4[e] = *(const float4 *)(ap + 16 * e);
   }
-  for (int d = 32; d >= 1; d >>= 1) mx = fmaxf(mx, __shfl_xor(mx, d));
-  if (lane == 0) red[wv] = mx;
-  __syncthreads();
-  mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-  __syncthreads();
-  float sum = 0.f;
+  f32x4 acc[MT];
+  float4 b4[8];
+  if (wv < T) {
+    const float *bp = ksrc + (size_t)min(16 * wv + n, nb - 1) * kHeadDim + 4 * g;
 #pragma unroll
-  for (int n = 0; n < PER; ++n) {
-    x[n] = __builtin_amdgcn_exp2f(x[n] - mx);
-    sum += x[n];
+    for (int e = 0; e < 8; ++e) b4[e] = *(const float4 *)(bp + 16 * e);
   }
-  for (int d = 32; d >= 1; d >>= 1) sum += __shfl_xor(sum, d);
-  if (lane == 0) red[wv] = sum;
-  __syncthreads();
-  sum = (red[0] + red[1]) + (red[2] + red[3]);
-  const float inv = 1.0f / sum;
 #pragma unroll
-  for (int n = 0; n < PER; ++n) {
-    const int C = tid + 256 * n;
-    if (C < nb) row[C] = (C <= R) ? x[n] * inv : 0.f;
+  for (int k = 0; k < MT; ++k) {
+    const int tc = 4 * k + wv;
+    if (tc < T) {
+      float4 bn[8];
+      if (tc + 4 < T) {
+        const float *bp = ksrc + (size_t)min(16 * (tc + 4) + n, nb - 1) * kHeadDim + 4 * g;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) bn[e] = *(const float4 *)(bp + 16 * e);
+      }
+      f32x4 d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        d = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[e].x, b4[e].x, d, 0, 0, 0);
+        d = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[e].y, b4[e].y, d, 0, 0, 0);
+        d = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[e].z, b4[e].z, d, 0, 0, 0);
+        d = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[e].w, b4[e].w, d, 0, 0, 0);
+      }
+      const int C = 16 * tc + n;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) acc[k][r] = (C <= R0 + 4 * g + r) ? d[r] * c2 : -INFINITY;
+      if (tc + 4 < T) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) b4[e] = bn[e];
+      }
+    } else {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) acc[k][r] = -INFINITY;
+    }
+  }
+  // row maxima: over this lane's tiles, the 16 lanes of a group, the four waves
+  float mx[4], sm[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    float v = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < MT; ++k) v = fmaxf(v, acc[k][r]);
+#pragma unroll
+    for (int d = 8; d >= 1; d >>= 1) v = fmaxf(v, __shfl_xor(v, d));
+    mx[r] = v;
+  }
+  if (n == 0) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) red[0][wv][4 * g + r] = mx[r];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int row = 4 * g + r;
+    mx[r] = fmaxf(fmaxf(red[0][0][row], red[0][1][row]), fmaxf(red[0][2][row], red[0][3][row]));
+  }
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    float v = 0.f;
+#pragma unroll
+    for (int k = 0; k < MT; ++k) {
+      acc[k][r] = __builtin_amdgcn_exp2f(acc[k][r] - mx[r]);  // column 0 is kept in every row: mx is finite
+      v += acc[k][r];
+    }
+#pragma unroll
+    for (int d = 8; d >= 1; d >>= 1) v += __shfl_xor(v, d);
+    sm[r] = v;
+  }
+  if (n == 0) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) red[1][wv][4 * g + r] = sm[r];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int row = 4 * g + r;
+    sm[r] = 1.0f / ((red[1][0][row] + red[1][1][row]) + (red[1][2][row] + red[1][3][row]));
+  }
+  float *dst = blk + (size_t)h * nb * nb;
+#pragma unroll
+  for (int k = 0; k < MT; ++k) {
+    const int tc = 4 * k + wv;
+    if (tc < T) {
+      const int C = 16 * tc + n;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int R = R0 + 4 * g + r;
+        if (R < nb && C < nb) dst[(size_t)R * nb + C] = acc[k][r] * sm[r];
+      }
+    }
+  }
+  // zeros right of the strip's last tile
+  const int c0 = 16 * T;
+  for (int r = 0; r < 16; ++r) {
+    const int R = R0 + r;
+    if (R >= nb) break;
+    for (int C = c0 + tid; C < nb; C += 256) dst[(size_t)R * nb + C] = 0.f;
   }
 }
 
@@ -384,15 +559,21 @@ __global__ __launch_bounds__(256) void block_softmax_kernel(Shape sh, float *blk
 
 hipError_t launch_estimate(const Shape &sh, const Workspace &ws, const uint16_t *Q,
                            const uint16_t *K, sa_scores out, hipStream_t st) {
-  const float c = sh.scale * 1.4426950408889634f;
+  const float c = sh.scale * kLog2e;
+  float *bias = (float *)ws.stats;
+  q_block_mean_kernel<<<dim3(sh.nb, sh.Hq), 256, 0, st>>>(Q, sh, ws.qblk);
   const dim3 wgrid(sh.nchunks, sh.Hkv, (sh.g + 3) / 4);
-  window_stats_kernel<<<wgrid, 256, 0, st>>>(Q, K, sh, c, ws.part, out.s);
-  window_stats_reduce_kernel<<<sh.Hq, 1024, 0, st>>>(ws.part, sh.nchunks, sh.w, ws.stats);
-  window_scores_kernel<<<wgrid, 256, 0, st>>>(Q, K, sh, c, ws.stats, out.v, out.s);
-  block_mean_kernel<<<dim3(sh.nb, sh.Hq + sh.Hkv), 256, 0, st>>>(Q, K, sh, ws.qblk, ws.kblk);
-  const int nt = (sh.nb + 63) / 64;
-  block_logits_kernel<<<dim3(nt, nt, sh.Hq), 256, 0, st>>>(ws.qblk, ws.kblk, sh, out.blk);
-  block_softmax_kernel<<<dim3(sh.nb, sh.Hq), 256, 0, st>>>(sh, out.blk);
+  window_stats_kernel<<<wgrid, 256, 0, st>>>(Q, K, sh, c, ws.part, out.s, ws.kblk);
+  window_stats_reduce_kernel<<<sh.Hq, 1024, 0, st>>>(ws.part, sh.nchunks, sh.w, bias);
+  window_scores_kernel<<<wgrid, 256, 0, st>>>(Q, K, sh, c, bias, out.v, out.s);
+  const dim3 bgrid((sh.nb + 15) / 16, sh.Hq);
+  const int tiles_per_wave = ((sh.nb + 15) / 16 + 3) / 4;
+  if (tiles_per_wave <= 16)
+    block_map_kernel<16><<<bgrid, 256, 0, st>>>(ws.qblk, ws.kblk, sh, c, out.blk);
+  else if (tiles_per_wave <= 32)
+    block_map_kernel<32><<<bgrid, 256, 0, st>>>(ws.qblk, ws.kblk, sh, c, out.blk);
+  else
+    block_map_kernel<64><<<bgrid, 256, 0, st>>>(ws.qblk, ws.kblk, sh, c, out.blk);
   return hipGetLastError();
 }
 

@@ -10,7 +10,7 @@ namespace sa {
 constexpr int kHeadDim = 128;
 constexpr int kMaxHeads = 128;
 constexpr int kWin = 64;          // rows of the last-query window the estimator tiles for
-constexpr int kChunk = 256;       // keys per estimator workgroup
+constexpr int kChunk = 512;       // keys per estimator workgroup (window passes)
 constexpr int kMaxSeq = 262144;   // key-tile bitmaps of the attention kernel cover this many keys
 
 struct Override { int8_t pat[kMaxHeads]; };
