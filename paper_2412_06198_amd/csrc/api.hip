@@ -11,6 +11,7 @@ struct sa_ctx {
   sa_config cfg;
   sa::Shape sh;
   sa::Workspace ws;
+  sa::Fork fork;
   bool have_ws;
   size_t ws_bytes;
   size_t off[10];
@@ -139,6 +140,23 @@ sa_status sa_create(const sa_config *cfg, sa_ctx **out) {
     s.n_cu = ncu;
   }
   s.scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)sa::kHeadDim);
+  // Side stream of the estimator (default priority).  Without a usable device the creation
+  // fails and the context simply enqueues everything on the caller's stream.
+  c->fork = sa::Fork{nullptr, nullptr, nullptr, nullptr};
+  if (hipStreamCreateWithFlags(&c->fork.aux, hipStreamNonBlocking) == hipSuccess) {
+    if (hipEventCreateWithFlags(&c->fork.fork, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&c->fork.mid, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&c->fork.join, hipEventDisableTiming) != hipSuccess) {
+      if (c->fork.fork) (void)hipEventDestroy(c->fork.fork);
+      if (c->fork.mid) (void)hipEventDestroy(c->fork.mid);
+      if (c->fork.join) (void)hipEventDestroy(c->fork.join);
+      (void)hipStreamDestroy(c->fork.aux);
+      c->fork = sa::Fork{nullptr, nullptr, nullptr, nullptr};
+    }
+  } else {
+    c->fork.aux = nullptr;
+  }
+  (void)hipGetLastError();
   c->have_ws = false;
   c->err[0] = 0;
   carve(c);
@@ -146,7 +164,16 @@ sa_status sa_create(const sa_config *cfg, sa_ctx **out) {
   return SA_OK;
 }
 
-void sa_destroy(sa_ctx *ctx) { delete ctx; }
+void sa_destroy(sa_ctx *ctx) {
+  if (!ctx) return;
+  if (ctx->fork.aux) {
+    (void)hipEventDestroy(ctx->fork.fork);
+    (void)hipEventDestroy(ctx->fork.mid);
+    (void)hipEventDestroy(ctx->fork.join);
+    (void)hipStreamDestroy(ctx->fork.aux);
+  }
+  delete ctx;
+}
 
 sa_status sa_scores_bytes(const sa_ctx *c, size_t out[3]) {
   if (!c || !out) return SA_ERR_INVALID_ARG;
@@ -205,7 +232,7 @@ sa_status sa_estimate_patterns(sa_ctx *c, const void *Q, const void *K, sa_score
   if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)out.blk) & 15) return fail(c, SA_ERR_INVALID_ARG, "Q, K, blk must be 16-byte aligned");
   if (!c->have_ws) return fail(c, SA_ERR_INVALID_ARG, "no workspace attached");
   return hip_result(c, sa::launch_estimate(c->sh, c->ws, (const uint16_t *)Q, (const uint16_t *)K, out,
-                                           (hipStream_t)stream));
+                                           (hipStream_t)stream, c->fork));
 }
 
 sa_status sa_build_index(sa_ctx *c, sa_scores in, const int32_t *override_host, sa_index out,

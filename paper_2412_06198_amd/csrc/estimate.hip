@@ -255,34 +255,35 @@ __global__ __launch_bounds__(256) void window_stats_kernel(const uint16_t *__res
 
 // combine the per-chunk partials into bias[i] = max_i + log2(sum_i) (log2 domain), so that a
 // window weight is exp2(logit * scale * log2e - bias).  Rows past the window get +inf (weight 0).
-// grid Hq, 1024 threads = 16 chunk slices x 64 window rows.
+// grid (Hq, 4), 1024 threads = 64 chunk slices x 16 window rows.
 __global__ __launch_bounds__(1024) void window_stats_reduce_kernel(const float2 *__restrict__ part,
                                                                   int nchunks, int w,
                                                                   float *__restrict__ bias) {
-  __shared__ float redm[16][kWin];
-  __shared__ float redz[16][kWin];
-  const int hq = blockIdx.x, i = threadIdx.x & 63, sl = threadIdx.x >> 6;
+  __shared__ float red[64][17];
+  const int hq = blockIdx.x, il = threadIdx.x & 15, sl = threadIdx.x >> 4;
+  const int i = 16 * blockIdx.y + il;
   const float2 *p = part + (size_t)hq * nchunks * kWin + i;
   float M = -INFINITY;
   if (i < w)
-    for (int cidx = sl; cidx < nchunks; cidx += 16) M = fmaxf(M, p[(size_t)cidx * kWin].x);
-  redm[sl][i] = M;
+    for (int cidx = sl; cidx < nchunks; cidx += 64) M = fmaxf(M, p[(size_t)cidx * kWin].x);
+  red[sl][il] = M;
   __syncthreads();
   float Mt = -INFINITY;
-#pragma unroll
-  for (int k = 0; k < 16; ++k) Mt = fmaxf(Mt, redm[k][i]);
+#pragma unroll 16
+  for (int k = 0; k < 64; ++k) Mt = fmaxf(Mt, red[k][il]);
+  __syncthreads();
   float Z = 0.f;
   if (i < w)
-    for (int cidx = sl; cidx < nchunks; cidx += 16) {
+    for (int cidx = sl; cidx < nchunks; cidx += 64) {
       const float2 e = p[(size_t)cidx * kWin];
       if (e.x != -INFINITY) Z += e.y * __builtin_amdgcn_exp2f(e.x - Mt);
     }
-  redz[sl][i] = Z;
+  red[sl][il] = Z;
   __syncthreads();
   if (sl == 0) {
     float Zt = 0.f;
-#pragma unroll
-    for (int k = 0; k < 16; ++k) Zt += redz[k][i];
+#pragma unroll 16
+    for (int k = 0; k < 64; ++k) Zt += red[k][il];
     bias[(size_t)hq * kWin + i] = i < w ? Mt + __builtin_amdgcn_logf(Zt) : INFINITY;  // v_log_f32 = log2
   }
 }
@@ -427,21 +428,39 @@ __global__ __launch_bounds__(256) void window_scores_kernel(const uint16_t *__re
 // blk[h][R][C] = softmax over C <= R of scale * Qblk[R].Kblk[C]; entries C > R are 0.
 // One workgroup = 16 rows of one head.  v_mfma_f32_16x16x4_f32 forms 16x16 logit tiles
 // (lane l: column l%16, rows 4(l/16) + r); the column tiles of the strip go round-robin to the
-// four waves and stay in registers (MT tiles per wave) until the row maxima and sums are known,
+// eight waves and stay in registers (MT tiles per wave) until the row maxima and sums are known,
 // so blk is written exactly once.  The contraction index is split so that MFMA step (e, x) of
 // lane group g = l/16 takes element 16e + 4g + x of a row: one load instruction then reads 64
-// contiguous bytes of each of the 16 rows.
-// grid (ceil(nb/16), Hq), 256 threads; strips are taken longest first.
+// contiguous bytes of each of the 16 rows.  Eight waves (and few registers each) rather than
+// four: the operand reads come from another XCD's writes, and only occupancy hides them.
+// grid ceil(nb/16) * Hq, 512 threads; strips are taken longest first.
+constexpr int kMapWaves = 8;
+
 template <int MT>
-__global__ __launch_bounds__(256) void block_map_kernel(const float *__restrict__ qblk,
-                                                        const float *__restrict__ kblk, Shape sh,
-                                                        float c2, float *__restrict__ blk) {
-  __shared__ float red[2][4][16];
+__global__ __launch_bounds__(64 * kMapWaves, (MT <= 8 ? 4 : 2)) void block_map_kernel(const float *__restrict__ qblk,
+                                                                   const float *__restrict__ kblk,
+                                                                   Shape sh, float c2,
+                                                                   float *__restrict__ blk) {
+  __shared__ float red[2][kMapWaves][16];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 15, g = lane >> 4;
   const int nb = sh.nb;
-  const int strip = (int)gridDim.x - 1 - (int)blockIdx.x, h = blockIdx.y;
+  // Consecutive workgroup ids land on consecutive XCDs.  While Hkv is a multiple of 8, KV head k
+  // is served by XCD k % 8 only, so that the L2 of an XCD holds the block means of one KV head at
+  // a time instead of all of them.
+  const int nstrips = (nb + 15) / 16;
+  const int L = blockIdx.x;
+  int strip, h;
+  if (sh.Hkv % 8 == 0) {
+    const int x = L & 7, s = L >> 3, hx = sh.Hq / 8;  // hx heads per XCD
+    const int hl = s % hx;
+    strip = nstrips - 1 - s / hx;
+    h = (x + 8 * (hl / sh.g)) * sh.g + hl % sh.g;
+  } else {
+    strip = nstrips - 1 - L % nstrips;
+    h = L / nstrips;
+  }
   const int R0 = 16 * strip;
   const int T = strip + 1;  // column tiles 0..strip hold every C <= R of this strip
   const float *qsrc = qblk + (size_t)h * nb * kHeadDim;
@@ -462,11 +481,11 @@ __global__ __launch_bounds__(256) void block_map_kernel(const float *__restrict_
   }
 #pragma unroll
   for (int k = 0; k < MT; ++k) {
-    const int tc = 4 * k + wv;
+    const int tc = kMapWaves * k + wv;
     if (tc < T) {
       float4 bn[8];
-      if (tc + 4 < T) {
-        const float *bp = ksrc + (size_t)min(16 * (tc + 4) + n, nb - 1) * kHeadDim + 4 * g;
+      if (tc + kMapWaves < T) {
+        const float *bp = ksrc + (size_t)min(16 * (tc + kMapWaves) + n, nb - 1) * kHeadDim + 4 * g;
 #pragma unroll
         for (int e = 0; e < 8; ++e) bn[e] = *(const float4 *)(bp + 16 * e);
       }
@@ -481,7 +500,7 @@ __global__ __launch_bounds__(256) void block_map_kernel(const float *__restrict_
       const int C = 16 * tc + n;
 #pragma unroll
       for (int r = 0; r < 4; ++r) acc[k][r] = (C <= R0 + 4 * g + r) ? d[r] * c2 : -INFINITY;
-      if (tc + 4 < T) {
+      if (tc + kMapWaves < T) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) b4[e] = bn[e];
       }
@@ -490,7 +509,7 @@ __global__ __launch_bounds__(256) void block_map_kernel(const float *__restrict_
       for (int r = 0; r < 4; ++r) acc[k][r] = -INFINITY;
     }
   }
-  // row maxima: over this lane's tiles, the 16 lanes of a group, the four waves
+  // row maxima: over this lane's tiles, the 16 lanes of a group, the eight waves
   float mx[4], sm[4];
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
@@ -508,8 +527,10 @@ __global__ __launch_bounds__(256) void block_map_kernel(const float *__restrict_
   __syncthreads();
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
-    const int row = 4 * g + r;
-    mx[r] = fmaxf(fmaxf(red[0][0][row], red[0][1][row]), fmaxf(red[0][2][row], red[0][3][row]));
+    float v = red[0][0][4 * g + r];
+#pragma unroll
+    for (int k = 1; k < kMapWaves; ++k) v = fmaxf(v, red[0][k][4 * g + r]);
+    mx[r] = v;
   }
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
@@ -530,13 +551,15 @@ __global__ __launch_bounds__(256) void block_map_kernel(const float *__restrict_
   __syncthreads();
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
-    const int row = 4 * g + r;
-    sm[r] = 1.0f / ((red[1][0][row] + red[1][1][row]) + (red[1][2][row] + red[1][3][row]));
+    float v = red[1][0][4 * g + r];
+#pragma unroll
+    for (int k = 1; k < kMapWaves; ++k) v += red[1][k][4 * g + r];
+    sm[r] = 1.0f / v;
   }
   float *dst = blk + (size_t)h * nb * nb;
 #pragma unroll
   for (int k = 0; k < MT; ++k) {
-    const int tc = 4 * k + wv;
+    const int tc = kMapWaves * k + wv;
     if (tc < T) {
       const int C = 16 * tc + n;
 #pragma unroll
@@ -551,29 +574,49 @@ __global__ __launch_bounds__(256) void block_map_kernel(const float *__restrict_
   for (int r = 0; r < 16; ++r) {
     const int R = R0 + r;
     if (R >= nb) break;
-    for (int C = c0 + tid; C < nb; C += 256) dst[(size_t)R * nb + C] = 0.f;
+    for (int C = c0 + tid; C < nb; C += 64 * kMapWaves) dst[(size_t)R * nb + C] = 0.f;
   }
 }
 
 }  // namespace
 
 hipError_t launch_estimate(const Shape &sh, const Workspace &ws, const uint16_t *Q,
-                           const uint16_t *K, sa_scores out, hipStream_t st) {
+                           const uint16_t *K, sa_scores out, hipStream_t st, const Fork &fk) {
   const float c = sh.scale * kLog2e;
   float *bias = (float *)ws.stats;
-  q_block_mean_kernel<<<dim3(sh.nb, sh.Hq), 256, 0, st>>>(Q, sh, ws.qblk);
+  // Two chains with complementary limits run side by side: the Q chain (block means of Q: HBM
+  // bandwidth; block map: latency of many small L2 reads) on the context's side stream, the K
+  // chain (both window passes: exp and vector ALU work on a quarter of the bytes) on the caller's
+  // stream.  The side stream forks from the caller's stream at entry and joins it at exit, so
+  // towards the caller the call behaves like a sequence of kernels on the given stream.
+  hipStream_t sq = st;
+  hipError_t e;
+  if (fk.aux) {
+    if ((e = hipEventRecord(fk.fork, st)) != hipSuccess) return e;
+    if ((e = hipStreamWaitEvent(fk.aux, fk.fork, 0)) != hipSuccess) return e;
+    sq = fk.aux;
+  }
+  q_block_mean_kernel<<<dim3(sh.nb, sh.Hq), 256, 0, sq>>>(Q, sh, ws.qblk);
   const dim3 wgrid(sh.nchunks, sh.Hkv, (sh.g + 3) / 4);
   window_stats_kernel<<<wgrid, 256, 0, st>>>(Q, K, sh, c, ws.part, out.s, ws.kblk);
-  window_stats_reduce_kernel<<<sh.Hq, 1024, 0, st>>>(ws.part, sh.nchunks, sh.w, bias);
-  window_scores_kernel<<<wgrid, 256, 0, st>>>(Q, K, sh, c, bias, out.v, out.s);
-  const dim3 bgrid((sh.nb + 15) / 16, sh.Hq);
-  const int tiles_per_wave = ((sh.nb + 15) / 16 + 3) / 4;
-  if (tiles_per_wave <= 16)
-    block_map_kernel<16><<<bgrid, 256, 0, st>>>(ws.qblk, ws.kblk, sh, c, out.blk);
-  else if (tiles_per_wave <= 32)
-    block_map_kernel<32><<<bgrid, 256, 0, st>>>(ws.qblk, ws.kblk, sh, c, out.blk);
+  if (fk.aux) {  // the block map needs the K block means of the stats pass
+    if ((e = hipEventRecord(fk.mid, st)) != hipSuccess) return e;
+    if ((e = hipStreamWaitEvent(fk.aux, fk.mid, 0)) != hipSuccess) return e;
+  }
+  const dim3 bgrid((sh.nb + 15) / 16 * sh.Hq);
+  const int tiles_per_wave = ((sh.nb + 15) / 16 + kMapWaves - 1) / kMapWaves;
+  if (tiles_per_wave <= 8)
+    block_map_kernel<8><<<bgrid, 64 * kMapWaves, 0, sq>>>(ws.qblk, ws.kblk, sh, c, out.blk);
+  else if (tiles_per_wave <= 16)
+    block_map_kernel<16><<<bgrid, 64 * kMapWaves, 0, sq>>>(ws.qblk, ws.kblk, sh, c, out.blk);
   else
-    block_map_kernel<64><<<bgrid, 256, 0, st>>>(ws.qblk, ws.kblk, sh, c, out.blk);
+    block_map_kernel<32><<<bgrid, 64 * kMapWaves, 0, sq>>>(ws.qblk, ws.kblk, sh, c, out.blk);
+  window_stats_reduce_kernel<<<dim3(sh.Hq, kWin / 16), 1024, 0, st>>>(ws.part, sh.nchunks, sh.w, bias);
+  window_scores_kernel<<<wgrid, 256, 0, st>>>(Q, K, sh, c, bias, out.v, out.s);
+  if (fk.aux) {
+    if ((e = hipEventRecord(fk.join, fk.aux)) != hipSuccess) return e;
+    if ((e = hipStreamWaitEvent(st, fk.join, 0)) != hipSuccess) return e;
+  }
   return hipGetLastError();
 }
 

@@ -38,8 +38,13 @@ struct Workspace {
 
 size_t index_scratch_bytes(int n_heads);
 
+// Side stream of a context with the events that fork it from and join it back into the caller's
+// stream inside one call (the estimator runs its Q chain beside its K chain).  aux == nullptr:
+// everything is enqueued on the caller's stream.
+struct Fork { hipStream_t aux; hipEvent_t fork, mid, join; };
+
 hipError_t launch_estimate(const Shape &sh, const Workspace &ws, const uint16_t *Q,
-                           const uint16_t *K, sa_scores out, hipStream_t st);
+                           const uint16_t *K, sa_scores out, hipStream_t st, const Fork &fk);
 hipError_t launch_build_index(const Shape &sh, const Workspace &ws, sa_scores in,
                               const Override &ov, sa_index out, hipStream_t st);
 hipError_t launch_sparse_prefill(const Shape &sh, const Workspace &ws, const uint16_t *Q,
