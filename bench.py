@@ -113,7 +113,7 @@ def run_workload(name, steps, warmup, layers, with_cpu, sample_rows):
             if pp >= 0:
                 confusion[pp, ch] += 1
     f_mask = 4.0 * d * float(np.mean(kept))
-    f_tiles = 4.0 * d * float(np.mean(tiles)) * 32 * 64
+    f_tiles = 4.0 * d * float(np.mean(tiles)) * 32 * 32   # counter unit: one 32 x 32 sub-tile
     f_dense = 4.0 * d * Hq * N * (N + 1) / 2.0
     nb = N // b
     est_bytes = 2 * Hkv * N * d + 2 * Hq * N * d + 2 * Hq * w * d + 8 * Hq * N + 4 * Hq * nb * nb
@@ -151,7 +151,8 @@ def main():
     ap.add_argument("--layers", type=int, default=2, help="distinct seeded layers kept resident (cfg5 sweep: 32)")
     ap.add_argument("--also", default="cfg3", help="second workload reported under 'also' ('' to skip)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--sample-rows", type=int, default=256)
+    ap.add_argument("--sample-rows", type=int, default=16384,
+                    help="rows per head of the oracle's masked attention in the cpu_baseline leg (about 10 s at 128K)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy a few times (reference for HBM byte counters)")
     a = ap.parse_args()

@@ -125,8 +125,9 @@ sa_status sa_sparse_prefill(sa_ctx *ctx, const void *Q, const void *K, const voi
 
 /* Same computation and output as sa_sparse_prefill, plus work accounting for
  * the FLOP figures of a benchmark: adds to counters_dev[0] the number of
- * (wave, key tile) pairs the kernel multiplied (32 queries x 64 keys each) and
- * to counters_dev[1] the number of kept (query, key) pairs, |M| of the sparse
+ * 32-query x 32-key sub-tiles the kernel multiplied (a 64-key tile of one wave
+ * counts 2, a selected diagonal of one wave counts 1; 4*head_dim*32*32 FLOP
+ * each) and to counters_dev[1] the number of kept (query, key) pairs, |M| of the sparse
  * softmax of Alg. 2 / Alg. 3.  counters_dev: DEVICE uint64[2], zeroed by the
  * caller.  Slower than sa_sparse_prefill (atomics); never time it. */
 sa_status sa_sparse_prefill_counted(sa_ctx *ctx, const void *Q, const void *K, const void *V,

@@ -220,7 +220,7 @@ class Session:
         sa_sparse_prefill(self.ctx, Q, K, V, self.index(), O, self.stream())
 
     def prefill_counted(self, Q, K, V, O):
-        """Returns (active wave-tiles, kept query-key pairs) of one prefill call."""
+        """Returns (32x32 sub-tiles multiplied, kept query-key pairs) of one prefill call."""
         cnt = self.torch.zeros(2, dtype=self.torch.int64, device=self.device)
         sa_sparse_prefill_counted(self.ctx, Q, K, V, self.index(), O, cnt, self.stream())
         self.torch.cuda.synchronize(self.device)

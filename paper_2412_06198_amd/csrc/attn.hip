@@ -38,7 +38,7 @@ struct AttnArgs {
   float c;  // softmax scale * log2(e)
   unsigned int *queue;           // [8] work-queue heads, zeroed by index_bitmaps_kernel
   int n_items;
-  unsigned long long *counters;  // instrumentation only: {active wave-tiles, kept (query,key) pairs}
+  unsigned long long *counters;  // instrumentation only: {32x32 sub-tiles multiplied, kept (query,key) pairs}
 };
 
 // Membership bitmaps of the selected columns and diagonal offsets, one block per head.

@@ -94,7 +94,7 @@ def test_counters_match_oracle_mask_count():
     tiles, kept = ses.prefill_counted(Qd, Kd, Vd, O)
     ix = download_index(ses)
     assert kept == sum(orc.mask_count(N, b, h, ix) for h in range(Hq))
-    assert tiles * 32 * 64 >= kept
+    assert tiles * 32 * 32 >= kept
     O2 = torch.empty_like(Qd)
     ses.prefill(Qd, Kd, Vd, O2)
     torch.cuda.synchronize()
