@@ -27,19 +27,28 @@ constexpr float kLog2e = 1.4426950408889634f;
 __device__ inline float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
 
 // ------------------------------------------------------------------ Q block means
-// grid (nb, Hq), 256 threads: thread = (row group of 16, 16-byte column).
+// grid (nb, Hq), 256 threads: thread = (row group of 16, 16-byte column); all RPT = b/16 loads of
+// a thread are in flight before the first sum.  The kernel is pure HBM streaming and runs beside
+// the window passes (vector ALU bound): it is launched with kQMeanLdsPad bytes of unused dynamic
+// LDS so that it never holds more than a few wave slots of a compute unit.
+constexpr int kQMeanLdsPad = 40 * 1024;
+
+template <int RPT>
 __global__ __launch_bounds__(256) void q_block_mean_kernel(const uint16_t *__restrict__ Q, Shape sh,
                                                            float *__restrict__ qblk) {
   __shared__ float red[16][kHeadDim + 4];
   const int R = blockIdx.x, h = blockIdx.y, tid = threadIdx.x;
   const uint16_t *src = Q + (size_t)h * sh.q_hs + (size_t)R * sh.b * sh.q_rs;
   const int cc = tid & 15, rg = tid >> 4;
+  uint4 x[RPT];
+#pragma unroll
+  for (int n = 0; n < RPT; ++n) x[n] = *(const uint4 *)(src + (size_t)(rg + 16 * n) * sh.q_rs + cc * 8);
   float acc[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) acc[e] = 0.f;
-  for (int r = rg; r < sh.b; r += 16) {
-    const uint4 x = *(const uint4 *)(src + (size_t)r * sh.q_rs + cc * 8);
-    const uint32_t wds[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+  for (int n = 0; n < RPT; ++n) {
+    const uint32_t wds[4] = {x[n].x, x[n].y, x[n].z, x[n].w};
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       acc[2 * e] += bf16_bits_to_f32(wds[e] & 0xFFFFu);
@@ -596,7 +605,10 @@ hipError_t launch_estimate(const Shape &sh, const Workspace &ws, const uint16_t 
     if ((e = hipStreamWaitEvent(fk.aux, fk.fork, 0)) != hipSuccess) return e;
     sq = fk.aux;
   }
-  q_block_mean_kernel<<<dim3(sh.nb, sh.Hq), 256, 0, sq>>>(Q, sh, ws.qblk);
+  if (sh.b == 128)
+    q_block_mean_kernel<8><<<dim3(sh.nb, sh.Hq), 256, kQMeanLdsPad, sq>>>(Q, sh, ws.qblk);
+  else
+    q_block_mean_kernel<4><<<dim3(sh.nb, sh.Hq), 256, kQMeanLdsPad, sq>>>(Q, sh, ws.qblk);
   const dim3 wgrid(sh.nchunks, sh.Hkv, (sh.g + 3) / 4);
   window_stats_kernel<<<wgrid, 256, 0, st>>>(Q, K, sh, c, ws.part, out.s, ws.kblk);
   if (fk.aux) {  // the block map needs the K block means of the stats pass
