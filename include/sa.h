@@ -16,6 +16,11 @@
  *     workspace).  Sizes come from the *_bytes queries.  The library never
  *     allocates or frees device memory and never synchronises the host: the
  *     three compute calls enqueue kernels on the given HIP stream and return.
+ *     sa_estimate_patterns runs part of its kernels on a side stream that the
+ *     context owns (created by sa_create, default priority); that stream waits
+ *     for the given stream at entry and the given stream waits for it at exit,
+ *     so work enqueued on the given stream before and after the call is
+ *     ordered with all of it.
  *   - Errors are return codes.  Argument checks are synchronous;
  *     SA_ERR_HIP wraps a failed launch; sa_last_error gives a text.
  *     Unsupported shapes are rejected, nothing is silently padded.
