@@ -142,6 +142,71 @@ def run_workload(name, steps, warmup, layers, with_cpu, sample_rows):
     return res
 
 
+def run_sweep(steps):
+    """Dense (all-keys index) against sparse (estimate + index + attention) per layer, 4K ... 128K:
+    where the method starts to pay on this GPU (the paper puts that threshold at 16K-32K tokens
+    on its own hardware; Experimental Results, TTFT table and its discussion)."""
+    import numpy as np
+    import torch
+
+    import paper_2412_06198_amd as sa
+    from harness import gen
+
+    def up(bits):
+        return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).cuda()
+
+    rows = []
+    for N, b, keep in ((4096, 64, 0.10), (8192, 64, 0.125), (16384, 64, 0.125), (32768, 64, 0.06),
+                       (65536, 128, 0.04), (131072, 128, 0.03)):
+        wl = gen.scaled(gen.WORKLOADS["cfg3"], name=f"sweep{N}", seq_len=N, block=b, keep=keep, seed=7000 + N,
+                        hot_block=b)
+        data = gen.generate(wl)
+        Hq, Hkv, w, d = wl.n_q_heads, wl.n_kv_heads, wl.last_q, wl.head_dim
+        Q, K, V = up(data["Q"]), up(data["K"]), up(data["V"])
+        O = torch.empty_like(Q)
+        nb = N // b
+        res = {}
+        for kind in ("sparse", "dense"):
+            if kind == "sparse":
+                ses = sa.Session(Hq, Hkv, N, b, w, keep=keep)
+            else:  # every causal block kept: Triangular with the band as wide as the sequence
+                ses = sa.Session(Hq, Hkv, N, b, w, keep=keep, local_blocks=nb, k_blocks=nb * (nb + 1) // 2)
+
+            def step():
+                if kind == "sparse":
+                    ses.estimate(Q, K)
+                    ses.build_index(None)
+                else:
+                    pass
+                ses.prefill(Q, K, V, O)
+
+            if kind == "dense":
+                ses.estimate(Q, K)
+                ses.build_index([sa.SA_TRIANGULAR] * Hq)   # the index is built once, outside the timing
+            n = steps if N <= 32768 or kind == "sparse" else max(2, steps // 4)
+            for _ in range(2):
+                step()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(n):
+                step()
+            e1.record()
+            torch.cuda.synchronize()
+            res[kind] = e0.elapsed_time(e1) / n
+            ses.close()
+        f_dense = 4.0 * d * Hq * N * (N + 1) / 2.0
+        rows.append({"seq_len": N, "block": b, "keep": keep, "sparse_ms": round(res["sparse"], 4),
+                     "dense_ms": round(res["dense"], 4), "speedup": round(res["dense"] / res["sparse"], 3),
+                     "dense_TFLOPs": round(f_dense / res["dense"] / 1e9, 1)})
+        log(f"[sweep] N={N}: sparse {res['sparse']:.3f} ms, dense {res['dense']:.3f} ms "
+            f"({rows[-1]['dense_TFLOPs']} TFLOP/s), ratio {rows[-1]['speedup']}")
+        del Q, K, V, O
+        torch.cuda.empty_cache()
+    print(json.dumps({"sweep": "dense (all-keys index) vs sparse path per layer, Hq=32 Hkv=8 d=128, "
+                               "planted mix 25/50/25", "rows": rows}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -155,6 +220,8 @@ def main():
                     help="rows per head of the oracle's masked attention in the cpu_baseline leg (about 10 s at 128K)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy a few times (reference for HBM byte counters)")
+    ap.add_argument("--sweep", action="store_true",
+                    help="dense-vs-sparse time per layer from 4K to 128K tokens instead of the benchmark line")
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (heads shard without communication; "
@@ -175,6 +242,9 @@ def main():
     import paper_2412_06198_amd as sa
 
     sa.library()
+    if a.sweep:
+        run_sweep(a.steps)
+        return
     main_res = run_workload(a.workload, a.steps, a.warmup, a.layers, not a.no_cpu_baseline, a.sample_rows)
     also = None
     if a.also and a.also != a.workload:

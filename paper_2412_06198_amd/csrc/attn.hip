@@ -151,6 +151,16 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
   const int N = p.N;
   const int ilast = min(i0 + BQ, N) - 1;
 
+  // long-latency reads first: they overlap the construction of the tile list
+  bf16x8 qf[8];  // Q^T fragments: B operand, lane = query, 8 consecutive d per k-step half
+  {
+    const uint16_t *qrow = p.Q + (size_t)h * p.q_hs + (size_t)min(iq, N - 1) * p.q_rs;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qf[ks] = *(const bf16x8 *)(qrow + 16 * ks + 8 * gg);
+  }
+  const int nc = min(max(p.n_cols[h], 0), p.k_v);
+  const bool has_offs = p.n_offs[h] > 0;
+
   // ---- tile list of this row block -------------------------------------------------------
   const int nwords = ((ilast / BK + 1) + 31) / 32;
   for (int i = tid; i < nwords; i += 256) { need[i] = 0u; kept0[i] = 0u; kept1[i] = 0u; }
@@ -209,7 +219,6 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
   }
 
   // gathered columns: how many selected columns are visible to this query (ascending list)
-  const int nc = min(max(p.n_cols[h], 0), p.k_v);
   int cle;
   {
     const int32_t *colp = p.cols + (size_t)h * p.k_v;
@@ -231,7 +240,6 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
   const int ng = (call + BK - 1) / BK;
   const int ntot = ntr + ng;
   const bool has_cols = nc > 0;
-  const bool has_offs = p.n_offs[h] > 0;
 
   // ---- operands ------------------------------------------------------------------------------
   const uint16_t *__restrict__ Kh = p.K + (size_t)kvh * p.kv_hs;
@@ -240,13 +248,6 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
   const uint16_t *__restrict__ Vgh = p.Vg + (size_t)h * p.kvg_rows * p.kv_rs;
   const uint32_t *__restrict__ offbm = p.offbits + (size_t)h * (N / 32);
   const uint32_t *__restrict__ colbm = p.colbits + (size_t)h * (N / 32);
-
-  bf16x8 qf[8];  // Q^T fragments: B operand, lane = query, 8 consecutive d per k-step half
-  {
-    const uint16_t *qrow = p.Q + (size_t)h * p.q_hs + (size_t)min(iq, N - 1) * p.q_rs;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) qf[ks] = *(const bf16x8 *)(qrow + 16 * ks + 8 * gg);
-  }
 
   f32x16 oacc[4];
 #pragma unroll
@@ -463,7 +464,7 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
   // global memory straight into the A operand; V passes through a wave-private LDS tile for
   // the transposing read.  An entry is dropped when its key block is kept by the CSR or its
   // key is a selected column: those tiles already counted it.
-  __syncthreads();  // all waves are done with the shared tiles: reuse them as 4 private V tiles
+  if (has_offs) __syncthreads();  // all waves are done with the shared tiles: reuse them as 4 private V tiles
   if (has_offs && r0 < N) {
     const int32_t *__restrict__ offp = p.offs + (size_t)h * p.k_s;
     const int no = min(max(p.n_offs[h], 0), p.k_s);
