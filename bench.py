@@ -52,7 +52,7 @@ def cpu_baseline(orc, data, wl, bud, sample_rows):
     }
 
 
-def run_workload(name, steps, warmup, layers, with_cpu, sample_rows):
+def run_workload(name, steps, warmup, layers, with_cpu, sample_rows, with_dense=False):
     import numpy as np
     import torch
 
@@ -131,6 +131,26 @@ def run_workload(name, steps, warmup, layers, with_cpu, sample_rows):
         "pattern_confusion_planted_x_chosen": confusion.tolist(),
         "paper_context": {"ttft_s_whole_model_2xA5000": PAPER_TTFT_S.get(name)},
     }
+    if with_dense:
+        # the same kernel on an all-keys index (Triangular with the band as wide as the sequence):
+        # plain causal attention, the clean figure for the tile loop itself
+        Q, K, V, _ = resident[0]
+        dn = sa.Session(Hq, Hkv, N, b, w, keep=wl.keep, local_blocks=nb, k_blocks=nb * (nb + 1) // 2)
+        dn.estimate(Q, K)
+        dn.build_index([sa.SA_TRIANGULAR] * Hq)
+        for _ in range(2):
+            dn.prefill(Q, K, V, O)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(4):
+            dn.prefill(Q, K, V, O)
+        e1.record()
+        torch.cuda.synchronize()
+        t_dense = e0.elapsed_time(e1) / 4
+        res["dense_all_keys_index"] = {"ms": t_dense, "TFLOPs_causal": f_dense / t_dense / 1e9,
+                                       "frac_of_bf16_peak": f_dense / t_dense / 1e9 / PEAK_BF16_TFLOPS}
+        log(f"[{name}] dense (all-keys index) {t_dense:.3f} ms = {f_dense / t_dense / 1e9:.0f} TFLOP/s")
+        dn.close()
     if with_cpu:
         from oracle import oracle as orc
         bud = orc.default_budgets(N, b, wl.keep)
@@ -248,7 +268,8 @@ def main():
     main_res = run_workload(a.workload, a.steps, a.warmup, a.layers, not a.no_cpu_baseline, a.sample_rows)
     also = None
     if a.also and a.also != a.workload:
-        also = run_workload(a.also, max(a.steps, 20), a.warmup, min(a.layers, 2), False, a.sample_rows)
+        also = run_workload(a.also, max(a.steps, 20), a.warmup, min(a.layers, 2), False, a.sample_rows,
+                            with_dense=True)
 
     traffic = None
     tp = os.path.join(ROOT, "profiles", f"traffic_{a.workload}.json")
