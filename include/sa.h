@@ -79,9 +79,9 @@ typedef struct { float *v, *s, *blk; } sa_scores;
 /* Device index buffers written by sa_build_index, read by sa_sparse_prefill:
  *   pattern [H]            chosen sa_pattern
  *   n_cols  [H]            number of selected key columns
- *   cols    [H][k_vertical] ascending, -1 padded
+ *   cols    [H][k_vertical] strictly ascending (no repeats), -1 padded
  *   n_offs  [H]            number of selected diagonal offsets
- *   offs    [H][k_slash]   ascending, -1 padded
+ *   offs    [H][k_slash]   strictly ascending (no repeats), -1 padded
  *   rowptr  [H][nb+1]      block CSR row pointers
  *   blkcols [H][cap]       key-block ids, ascending within a row, -1 padded;
  *                          cap = sizes[6]/(4*H) from sa_index_bytes

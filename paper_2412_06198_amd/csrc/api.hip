@@ -14,7 +14,7 @@ struct sa_ctx {
   sa::Fork fork;
   bool have_ws;
   size_t ws_bytes;
-  size_t off[10];
+  size_t off[11];
   char err[256];
 };
 
@@ -50,6 +50,7 @@ void carve(sa_ctx *c) {
   c->off[7] = o; o += align256(kvg);
   c->off[8] = o; o += 256;
   c->off[9] = o; o += align256(sa::index_scratch_bytes(s.Hq));
+  c->off[10] = o; o += align256((size_t)s.Hq * (s.N / 32) * 4);
   c->ws_bytes = o;
 }
 
@@ -216,6 +217,7 @@ sa_status sa_set_workspace(sa_ctx *c, void *dev, size_t bytes) {
   c->ws.vg = (uint16_t *)(p + c->off[7]);
   c->ws.queue = (unsigned int *)(p + c->off[8]);
   c->ws.idx = (void *)(p + c->off[9]);
+  c->ws.colprefix = (int32_t *)(p + c->off[10]);
   c->have_ws = true;
   return SA_OK;
 }

@@ -31,6 +31,7 @@ struct AttnArgs {
   uint16_t *O;
   const int32_t *n_cols, *cols, *n_offs, *offs, *rowptr, *blkcols;
   const uint32_t *offbits, *colbits;
+  const int32_t *colprefix;  // [Hq][N/32] selected columns before each word of colbits
   uint16_t *Kg, *Vg;  // [Hq][kvg_rows][kv_rs] selected key columns, gathered once per call
   int kvg_rows;
   int Hq, Hkv, g, N, b, nb, nT, k_v, k_s, cap_b;
@@ -41,11 +42,12 @@ struct AttnArgs {
   unsigned long long *counters;  // instrumentation only: {32x32 sub-tiles multiplied, kept (query,key) pairs}
 };
 
-// Membership bitmaps of the selected columns and diagonal offsets, one block per head.
-__global__ void index_bitmaps_kernel(const int32_t *n_cols, const int32_t *cols,
+// Membership bitmaps of the selected columns and diagonal offsets, and the running count of
+// selected columns before each bitmap word, one block of 256 threads per head.
+__global__ __launch_bounds__(256) void index_bitmaps_kernel(const int32_t *n_cols, const int32_t *cols,
                                      const int32_t *n_offs, const int32_t *offs, int k_v, int k_s,
                                      int N, uint32_t *colbits, uint32_t *offbits,
-                                     unsigned int *queue) {
+                                     int32_t *colprefix, unsigned int *queue) {
   const int h = blockIdx.x, nw = N / 32;
   if (h == 0 && threadIdx.x < 8) queue[threadIdx.x] = 0u;
   for (int i = threadIdx.x; i < nw; i += blockDim.x) {
@@ -62,6 +64,26 @@ __global__ void index_bitmaps_kernel(const int32_t *n_cols, const int32_t *cols,
     const int o = offs[(size_t)h * k_s + i];
     if (o >= 0 && o < N) atomicOr(&offbits[(size_t)h * nw + (o >> 5)], 1u << (o & 31));
   }
+  // exclusive prefix popcount over the column bitmap: thread t owns a contiguous run of words
+  __shared__ int s_run[256];
+  __syncthreads();
+  const int tid = threadIdx.x, per = (nw + 255) / 256;
+  const int w0 = min(tid * per, nw), w1 = min(w0 + per, nw);
+  int mine = 0;
+  for (int w = w0; w < w1; ++w) mine += __popc(colbits[(size_t)h * nw + w]);
+  s_run[tid] = mine;
+  __syncthreads();
+  for (int d = 1; d < 256; d <<= 1) {
+    const int add = tid >= d ? s_run[tid - d] : 0;
+    __syncthreads();
+    s_run[tid] += add;
+    __syncthreads();
+  }
+  int run = s_run[tid] - mine;
+  for (int w = w0; w < w1; ++w) {
+    colprefix[(size_t)h * nw + w] = run;
+    run += __popc(colbits[(size_t)h * nw + w]);
+  }
 }
 
 __device__ inline uint32_t bits_word(const uint32_t *__restrict__ bm, int nw, int wi) {
@@ -74,6 +96,20 @@ __device__ inline uint64_t bits_window64(const uint32_t *__restrict__ bm, int nw
   const uint64_t lo = (uint64_t)bits_word(bm, nw, wi) | ((uint64_t)bits_word(bm, nw, wi + 1) << 32);
   const uint64_t hi = (uint64_t)bits_word(bm, nw, wi + 2);
   return sh ? ((lo >> sh) | (hi << (64 - sh))) : lo;
+}
+
+// Read-only words at a wave-uniform address: through the constant address space these become
+// scalar loads, which neither occupy the vector memory path nor count in vmcnt.
+typedef const uint32_t __attribute__((address_space(4))) *const_u32p;
+__device__ inline uint32_t uload(const void *p, int idx) { return ((const_u32p)(uintptr_t)p)[idx]; }
+
+// 32 bits of a bitmap starting at bit `pos` (may be negative or run past the end); pos wave-uniform.
+__device__ inline uint32_t bits_window32(const uint32_t *bm, int nw, int pos) {
+  const int wi = pos >> 5, sh = pos & 31;  // arithmetic shift: floor for negatives
+  uint32_t lo = uload(bm, min(max(wi, 0), nw - 1)), hi = uload(bm, min(max(wi + 1, 0), nw - 1));
+  lo = (wi >= 0 && wi < nw) ? lo : 0u;
+  hi = (wi + 1 >= 0 && wi + 1 < nw) ? hi : 0u;
+  return (uint32_t)(((uint64_t)lo | ((uint64_t)hi << 32)) >> sh);
 }
 
 // The selected key columns of every head, copied once into contiguous [k][d] buffers so that
@@ -160,6 +196,15 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
   }
   const int nc = min(max(p.n_cols[h], 0), p.k_v);
   const bool has_offs = p.n_offs[h] > 0;
+  // selected columns visible to this query = those up to its own position: the running count
+  // before its bitmap word plus the bits of that word up to the position (the list is ascending
+  // and without repeats, so this is also the query's cut in the gathered list)
+  int cle = 0;
+  if (nc > 0) {
+    const int key = min(iq, N - 1), wi = key >> 5;
+    const size_t bo = (size_t)h * (N / 32) + wi;
+    cle = p.colprefix[bo] + __popc(p.colbits[bo] & (0xFFFFFFFFu >> (31 - (key & 31))));
+  }
 
   // ---- tile list of this row block -------------------------------------------------------
   const int nwords = ((ilast / BK + 1) + 31) / 32;
@@ -218,19 +263,7 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
     if (lane == 0) s_ntiles = base;
   }
 
-  // gathered columns: how many selected columns are visible to this query (ascending list)
-  int cle;
-  {
-    const int32_t *colp = p.cols + (size_t)h * p.k_v;
-    int lo = 0, hi = nc;
-    const int key = min(iq, N - 1);
-    while (lo < hi) {
-      const int mid = (lo + hi) >> 1;
-      if (colp[mid] <= key) lo = mid + 1; else hi = mid;
-    }
-    cle = lo;
-  }
-  int cmax = cle;
+  int cmax = cle;  // gather tiles this wave needs: up to its last query's cut
   for (int d = 32; d >= 1; d >>= 1) cmax = max(cmax, __shfl_xor(cmax, d));
   if (lane == 0) s_cmax[wv] = cmax;
   __syncthreads();
@@ -328,7 +361,7 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
       const bool bk = (((wv < 2 ? kept0 : kept1)[kt >> 5] >> (kt & 31)) & 1u) != 0;
       const bool beyond = j0 > min(r0 + 31, N - 1);
       active = !beyond && bk;
-      const uint64_t vm = has_cols ? ((uint64_t)colbm[2 * kt] | ((uint64_t)colbm[2 * kt + 1] << 32)) : 0ull;
+      const uint64_t vm = has_cols ? ((uint64_t)uload(colbm, 2 * kt) | ((uint64_t)uload(colbm, 2 * kt + 1) << 32)) : 0ull;
       needmask = !(vm == 0 && j0 + 63 <= r0);
       km = ~0ull;
       if (active && needmask) {
@@ -461,103 +494,90 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
   // ---- selected diagonals: one 32-key tile per (wave, offset), no workgroup barriers -----------
   // For offset o the 32 queries of this wave need the 32 keys r0-o .. r0-o+31, and in
   // S^T = K Q^T (32 keys x 32 queries) the wanted entries are the main diagonal.  K goes from
-  // global memory straight into the A operand; V passes through a wave-private LDS tile for
-  // the transposing read.  An entry is dropped when its key block is kept by the CSR or its
-  // key is a selected column: those tiles already counted it.
-  if (has_offs) __syncthreads();  // all waves are done with the shared tiles: reuse them as 4 private V tiles
+  // global memory straight into the A operand; V is copied by the LDS DMA into a wave-private
+  // tile for the transposing read.  An entry is dropped when its key block is kept by the CSR
+  // or its key is a selected column: those tiles already counted it.
+  // Nothing here is reused, so the phase lives on memory latency: the reads of the next offset
+  // (column-bitmap words, K, V - in that order) are issued as soon as S^T has consumed the K
+  // registers, and each wave has two V tiles.
+  if (has_offs) __syncthreads();  // all waves are done with the shared tiles: reuse them as private V tiles
   if (has_offs && r0 < N) {
     const int32_t *__restrict__ offp = p.offs + (size_t)h * p.k_s;
     const int no = min(max(p.n_offs[h], 0), p.k_s);
     const int rmax = min(r0 + 31, N - 1);
-    int nd = 0;  // offsets are ascending: the usable ones (o <= last row of the wave) come first
-    while (nd < no && offp[nd] >= 0 && offp[nd] <= rmax) ++nd;
     int dl = lane;
     asm volatile("" : "+v"(dl));  // this phase's lane constants are born here, not before the tile loop
     const int q = dl & 31, gg = dl >> 5, lane = dl;
-    uint16_t *Vw = Vs[wv >> 1] + (wv & 1) * (32 * 128);
-    // the Q fragments move to the (now idle) K buffers: 8 KB per wave, read back one k-step at a
-    // time, so that their 32 registers can stage the next diagonal's K and V instead
-    uint16_t *Qw0 = Ks[wv >> 1] + (wv & 1) * (32 * 128);
-    unsigned qlane = lane * 8;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) *(bf16x8 *)&Qw0[qlane + ks * 512] = qf[ks];
+    int nd = 0;  // offsets are ascending: the usable ones (0 <= o <= last row of the wave) come first
+    for (int base = 0; base < no; base += 64) {
+      const int i = base + lane;
+      const int ov = i < no ? offp[i] : -1;
+      const unsigned long long bad = ~__ballot(i < no && ov >= 0 && ov <= rmax);
+      const int run = bad ? __ffsll(bad) - 1 : 64;
+      nd += run;
+      if (run < 64) break;
+    }
+    nd = __builtin_amdgcn_readfirstlane(nd);
+    // two 8 KB V tiles per wave: waves 0, 1 in the V buffers, waves 2, 3 in the K buffers
+    uint16_t *Vw0 = (wv < 2 ? &Vs[0][0] : &Ks[0][0]) + (wv & 1) * (2 * 32 * 128);
+    const unsigned ldsVw = (unsigned)(uintptr_t)(__attribute__((address_space(3))) uint16_t *)Vw0;
     const int rstar = 4 * (q >> 3) + (q & 3);        // register of S^T that holds key_local == q
     const bool holder = gg == ((q >> 2) & 1);        // ... in this half of the lane pair
-    const int vrow = lane >> 4, vch = lane & 15;     // V staging: rows vrow+4n, 16-byte chunk vch
-    const int vdst = vswz(vrow, vch);                // rows +4n keep (row & 3)
-    const uint16_t *Kq = Kh + 8 * gg, *Vq = Vh + 8 * vch;
-    bf16x8 ka0, ka1, ka2, ka3, ka4, ka5, ka6, ka7;
-    uint4 vs0, vs1, vs2, vs3, vs4, vs5, vs6, vs7;
-#define SA_DIAG_LOAD_K(o)                                                          \
-  {                                                                                \
-    const int jr = min(max(r0 - (o) + q, 0), N - 1);                               \
-    const uint16_t *kr = Kq + (size_t)jr * p.kv_rs;                                \
-    ka0 = *(const bf16x8 *)(kr); ka1 = *(const bf16x8 *)(kr + 16);                 \
-    ka2 = *(const bf16x8 *)(kr + 32); ka3 = *(const bf16x8 *)(kr + 48);            \
-    ka4 = *(const bf16x8 *)(kr + 64); ka5 = *(const bf16x8 *)(kr + 80);            \
-    ka6 = *(const bf16x8 *)(kr + 96); ka7 = *(const bf16x8 *)(kr + 112);           \
+    const int vrow = lane >> 4;                      // V copy: one instruction moves rows 4n + vrow
+    const unsigned vchunk = (unsigned)(((lane & 15) ^ (vrow << 2)) << 4);  // swizzle applied on the global side
+    const unsigned vfast = (unsigned)(vrow * (int)p.kv_rs * 2) + vchunk;
+    const uint16_t *Kq = Kh + 8 * gg;
+    const uint32_t *kw = wv < 2 ? kept0 : kept1;
+    bf16x8 kd[8];
+    uint32_t cw = 0u;
+#define SA_DIAG_ISSUE(o, stg)                                                                    \
+  {                                                                                              \
+    const int jb_ = r0 - (o);                                                                    \
+    if (has_cols) cw = bits_window32(colbm, N / 32, jb_);                                        \
+    const int jr_ = min(max(jb_ + q, 0), N - 1);                                                 \
+    const uint16_t *kr_ = Kq + (size_t)jr_ * p.kv_rs;                                            \
+    _Pragma("unroll") for (int k_ = 0; k_ < 8; ++k_) kd[k_] = *(const bf16x8 *)(kr_ + 16 * k_);  \
+    const unsigned lv_ = ldsVw + (stg) * (32 * 256);                                             \
+    if (jb_ >= 0 && jb_ + 31 < N) {                                                              \
+      const uint16_t *vb_ = Vh + (size_t)jb_ * p.kv_rs;                                          \
+      _Pragma("unroll") for (int n_ = 0; n_ < 8; ++n_)                                           \
+        SA_DMA16(vb_ + (size_t)(4 * n_) * p.kv_rs, vfast, lv_ + n_ * 1024);                      \
+    } else { /* rows outside the sequence: clamped copies, masked out by the validity test */    \
+      _Pragma("unroll") for (int n_ = 0; n_ < 8; ++n_) {                                         \
+        const int rb_ = min(max(jb_ + 4 * n_, 0), N - 1);                                        \
+        const int dr_ = min(max(jb_ + 4 * n_ + vrow, 0), N - 1) - rb_; /* >= 0 */                \
+        SA_DMA16(Vh + (size_t)rb_ * p.kv_rs, (unsigned)(dr_ * (int)p.kv_rs * 2) + vchunk,        \
+                 lv_ + n_ * 1024);                                                               \
+      }                                                                                          \
+    }                                                                                            \
   }
-#define SA_DIAG_LOAD_V(o)                                                          \
-  {                                                                                \
-    const int jb_ = r0 - (o);                                                      \
-    if (jb_ >= 0 && jb_ + 31 < N) {                                                \
-      const uint16_t *vp = Vq + (size_t)(jb_ + vrow) * p.kv_rs;                    \
-      const size_t st = 4 * (size_t)p.kv_rs;                                       \
-      vs0 = *(const uint4 *)(vp); vs1 = *(const uint4 *)(vp + st);                 \
-      vs2 = *(const uint4 *)(vp + 2 * st); vs3 = *(const uint4 *)(vp + 3 * st);    \
-      vs4 = *(const uint4 *)(vp + 4 * st); vs5 = *(const uint4 *)(vp + 5 * st);    \
-      vs6 = *(const uint4 *)(vp + 6 * st); vs7 = *(const uint4 *)(vp + 7 * st);    \
-    } else {                                                                       \
-      vs0 = *(const uint4 *)SA_VROW(jb_, 0); vs1 = *(const uint4 *)SA_VROW(jb_, 1); \
-      vs2 = *(const uint4 *)SA_VROW(jb_, 2); vs3 = *(const uint4 *)SA_VROW(jb_, 3); \
-      vs4 = *(const uint4 *)SA_VROW(jb_, 4); vs5 = *(const uint4 *)SA_VROW(jb_, 5); \
-      vs6 = *(const uint4 *)SA_VROW(jb_, 6); vs7 = *(const uint4 *)SA_VROW(jb_, 7); \
-    }                                                                              \
-  }
-#define SA_VROW(jb, n) (Vq + (size_t)min(max((jb) + vrow + 4 * (n), 0), N - 1) * p.kv_rs)
     if (nd > 0) {
-      const int o0 = __builtin_amdgcn_readfirstlane(offp[0]);
-      SA_DIAG_LOAD_K(o0);
-      SA_DIAG_LOAD_V(o0);
+      const int o0 = (int)uload(offp, 0);
+      SA_DIAG_ISSUE(o0, 0);
     }
     for (int e = 0; e < nd; ++e) {
-      const int o = __builtin_amdgcn_readfirstlane(offp[e]);
-      const int onext = __builtin_amdgcn_readfirstlane(offp[min(e + 1, nd - 1)]);
+      const int o = (int)uload(offp, e);
+      const int onext = (int)uload(offp, min(e + 1, nd - 1));
       const int jb = r0 - o;
-      asm volatile("" : "+v"(qlane));  // keeps the Q reads inside the loop (no hoisting into 32 registers)
-      const uint16_t *Qw = Qw0 + qlane;
-      *(uint4 *)&Vw[vdst] = vs0; *(uint4 *)&Vw[vdst + 4 * 128] = vs1;
-      *(uint4 *)&Vw[vdst + 8 * 128] = vs2; *(uint4 *)&Vw[vdst + 12 * 128] = vs3;
-      *(uint4 *)&Vw[vdst + 16 * 128] = vs4; *(uint4 *)&Vw[vdst + 20 * 128] = vs5;
-      *(uint4 *)&Vw[vdst + 24 * 128] = vs6; *(uint4 *)&Vw[vdst + 28 * 128] = vs7;
-      if (e + 1 < nd) SA_DIAG_LOAD_V(onext);
       f32x16 sd;
 #pragma unroll
       for (int r = 0; r < 16; ++r) sd[r] = 0.f;
-      sd = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka0, *(const bf16x8 *)&Qw[0 * 512], sd, 0, 0, 0);
-      sd = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka1, *(const bf16x8 *)&Qw[1 * 512], sd, 0, 0, 0);
-      sd = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka2, *(const bf16x8 *)&Qw[2 * 512], sd, 0, 0, 0);
-      sd = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka3, *(const bf16x8 *)&Qw[3 * 512], sd, 0, 0, 0);
-      sd = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka4, *(const bf16x8 *)&Qw[4 * 512], sd, 0, 0, 0);
-      sd = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka5, *(const bf16x8 *)&Qw[5 * 512], sd, 0, 0, 0);
-      sd = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka6, *(const bf16x8 *)&Qw[6 * 512], sd, 0, 0, 0);
-      sd = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka7, *(const bf16x8 *)&Qw[7 * 512], sd, 0, 0, 0);
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) sd = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kd[ks], qf[ks], sd, 0, 0, 0);
       float sv = sd[0];
 #pragma unroll
       for (int r = 1; r < 16; ++r) sv = (r == rstar) ? sd[r] : sv;
-      if (e + 1 < nd) SA_DIAG_LOAD_K(onext);
+      const bool cbit = (cw >> q) & 1u;
+      // the K registers and the other V tile (last read one offset ago) are free: next offset
+      if (e + 1 < nd) SA_DIAG_ISSUE(onext, (e + 1) & 1);
       // validity of (query iq, key iq - o)
       const int j = iq - o;
       bool valid = holder && j >= 0 && iq < N;
       {
         const int kta = max(jb, 0) >> 6, ktb = max(jb + 31, 0) >> 6;  // the (at most two) key tiles touched
-        const uint32_t *kept = wv < 2 ? kept0 : kept1;
-        const bool ba = (kept[kta >> 5] >> (kta & 31)) & 1u, bb = (kept[ktb >> 5] >> (ktb & 31)) & 1u;
+        const bool ba = (kw[kta >> 5] >> (kta & 31)) & 1u, bb = (kw[ktb >> 5] >> (ktb & 31)) & 1u;
         if (((max(j, 0) >> 6) == kta) ? ba : bb) valid = false;
-        if (has_cols) {
-          const uint32_t cw = (uint32_t)bits_window64(colbm, N / 32, jb);
-          if ((cw >> q) & 1u) valid = false;
-        }
+        if (has_cols && cbit) valid = false;
       }
       if constexpr (STATS) {
         unsigned long long kept_n = valid ? 1ull : 0ull;
@@ -583,7 +603,12 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
       const float pv = valid ? __builtin_amdgcn_exp2f(__builtin_fmaf(sv, p.c, -m_ref)) : 0.f;
       l_run += pv;
       const __bf16 pvb = (__bf16)pv, zb = (__bf16)0.f;
-      // P^T is diagonal: slot e of k-step u is register 8u+e
+      // V of this offset has landed once only the 16 reads of the next offset, all issued after
+      // it, are outstanding (the counted variant also has atomics in flight: wait for everything)
+      if (!STATS && e + 1 < nd) __builtin_amdgcn_s_waitcnt(0x4F70);  // vmcnt(16)
+      else __builtin_amdgcn_s_waitcnt(0x0F70);                       // vmcnt(0)
+      const uint16_t *Vw = Vw0 + (e & 1) * (32 * 128);
+      // P^T is diagonal: slot e2 of k-step u is register 8u+e2
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
         bf16x8 pb;
@@ -599,9 +624,7 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
         }
       }
     }
-#undef SA_DIAG_LOAD_K
-#undef SA_DIAG_LOAD_V
-#undef SA_VROW
+#undef SA_DIAG_ISSUE
   }
 
   // ---- epilogue: O[iq][32db + 8(r/4) + 4gg + r%4] = oacc / l -------------------------------------
@@ -633,14 +656,14 @@ hipError_t launch_sparse_prefill(const Shape &sh, const Workspace &ws, const uin
                                  const uint16_t *K, const uint16_t *V, sa_index idx, uint16_t *O,
                                  unsigned long long *counters, hipStream_t st) {
   index_bitmaps_kernel<<<sh.Hq, 256, 0, st>>>(idx.n_cols, idx.cols, idx.n_offs, idx.offs, sh.k_v,
-                                              sh.k_s, sh.N, ws.colbits, ws.offbits, ws.queue);
+                                              sh.k_s, sh.N, ws.colbits, ws.offbits, ws.colprefix, ws.queue);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   AttnArgs a;
   a.Q = Q; a.K = K; a.V = V; a.O = O;
   a.n_cols = idx.n_cols; a.cols = idx.cols; a.n_offs = idx.n_offs; a.offs = idx.offs;
   a.rowptr = idx.rowptr; a.blkcols = idx.blkcols;
-  a.offbits = ws.offbits; a.colbits = ws.colbits;
+  a.offbits = ws.offbits; a.colbits = ws.colbits; a.colprefix = ws.colprefix;
   a.Hq = sh.Hq; a.Hkv = sh.Hkv; a.g = sh.g; a.N = sh.N; a.b = sh.b; a.nb = sh.nb;
   a.nT = (sh.N + BQ - 1) / BQ;
   a.k_v = sh.k_v; a.k_s = sh.k_s; a.cap_b = sh.cap_b;

@@ -31,6 +31,7 @@ struct Workspace {
   float2 *part;                   // [Hq][nchunks][64] partial (max, sum) of the window rows
   float2 *stats;                  // [Hq][64] (max * scale*log2e, 1/sum)
   uint32_t *offbits, *colbits;    // [Hq][N/32] membership bitmaps of offs / cols
+  int32_t *colprefix;             // [Hq][N/32] number of selected columns before each word of colbits
   unsigned int *queue;            // [8] work-queue heads of the attention kernel
   void *idx;                      // per-head scratch of the index builder
   uint16_t *kg, *vg;              // [Hq][roundup64(k_v)][kv_rs] gathered K / V rows of the selected columns
