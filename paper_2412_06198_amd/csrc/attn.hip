@@ -153,9 +153,14 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
   // (consecutive workgroup ids land on consecutive XCDs): item id = queue + 8*k.  KV heads
   // rotate fastest in the item id, so a queue - and with it an XCD and its L2 - stays on one
   // KV head while Hkv is a multiple of 8.  The longest (last) row blocks come first.  A
-  // workgroup whose own queue is empty takes from the others, then exits.
+  // workgroup whose own queue is empty takes from the others, then exits.  The ticket for the
+  // next item of the home queue is drawn while the current item finishes, so its round trip is
+  // off the critical path.
   __shared__ int s_item;
   const int home = blockIdx.x & 7;
+  int ticket = 0;         // thread 0 only: position drawn from the home queue
+  bool home_open = true;  // thread 0 only: the home queue still had items at the last draw
+  if (threadIdx.x == 0) ticket = (int)atomicAdd(&p.queue[home], 1u);
   for (;;) {
   // Lane-derived constants are recomputed per item from an opaque copy of the thread id:
   // hoisted out of this loop they would stay live across every phase and spill.
@@ -165,7 +170,11 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
   __syncthreads();  // previous item fully retired: LDS work lists and tiles may be reused
   if (tid == 0) {
     int item = -1;
-    for (int qq = 0; qq < 8 && item < 0; ++qq) {
+    if (home_open) {
+      if (home + 8 * ticket < p.n_items) item = home + 8 * ticket;
+      else home_open = false;
+    }
+    for (int qq = 1; qq < 8 && item < 0; ++qq) {
       const int qn = (home + qq) & 7;
       if (qn + 8 * (int)__hip_atomic_load(&p.queue[qn], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= p.n_items)
         continue;
@@ -194,16 +203,26 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) qf[ks] = *(const bf16x8 *)(qrow + 16 * ks + 8 * gg);
   }
-  const int nc = min(max(p.n_cols[h], 0), p.k_v);
-  const bool has_offs = p.n_offs[h] > 0;
+  // the item's small reads sit at wave-uniform addresses: scalar loads, all in flight together
+  const int nc = min(max((int)uload(p.n_cols, h), 0), p.k_v);
+  const bool has_offs = (int)uload(p.n_offs, h) > 0;
+  // CSR entry ranges of the row blocks of this item: one at block 128, two (2*t128 for waves 0,1
+  // and 2*t128+1 for waves 2,3) at block 64
+  const int32_t *rp = p.rowptr + (size_t)h * (p.nb + 1);
+  const int Ra = p.b == BQ ? t128 : 2 * t128;
+  const bool two = p.b != BQ && Ra + 1 < p.nb;
+  const int ea0 = max((int)uload(rp, Ra), 0), ea1 = min((int)uload(rp, Ra + 1), p.cap_b);
+  const int eb0 = max((int)uload(rp, min(Ra + 1, p.nb)), 0), eb1 = min((int)uload(rp, min(Ra + 2, p.nb)), p.cap_b);
+  const int na = max(ea1 - ea0, 0), nbk = two ? max(eb1 - eb0, 0) : 0;
   // selected columns visible to this query = those up to its own position: the running count
   // before its bitmap word plus the bits of that word up to the position (the list is ascending
   // and without repeats, so this is also the query's cut in the gathered list)
-  int cle = 0;
-  if (nc > 0) {
+  int cle;
+  {
     const int key = min(iq, N - 1), wi = key >> 5;
     const size_t bo = (size_t)h * (N / 32) + wi;
     cle = p.colprefix[bo] + __popc(p.colbits[bo] & (0xFFFFFFFFu >> (31 - (key & 31))));
+    cle = nc > 0 ? cle : 0;
   }
 
   // ---- tile list of this row block -------------------------------------------------------
@@ -211,32 +230,18 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
   for (int i = tid; i < nwords; i += 256) { need[i] = 0u; kept0[i] = 0u; kept1[i] = 0u; }
   __syncthreads();
   {
-    const int32_t *rp = p.rowptr + (size_t)h * (p.nb + 1);
+    // one pass over the entries of both row blocks, so that their reads are in flight together
     const int32_t *bc = p.blkcols + (size_t)h * p.cap_b;
-    if (p.b == BQ) {
-      const int e0 = max(rp[t128], 0), e1 = min(rp[t128 + 1], p.cap_b);
-      for (int e = e0 + tid; e < e1; e += 256) {
-        const int C = bc[e];
-        if (C >= 0 && C <= t128) {
-          const int kt = 2 * C;  // two key tiles per 128-key block: adjacent bits of one word
-          atomicOr(&need[kt >> 5], 3u << (kt & 31));
-          atomicOr(&kept0[kt >> 5], 3u << (kt & 31));
-          atomicOr(&kept1[kt >> 5], 3u << (kt & 31));
-        }
-      }
-    } else {  // block 64: this workgroup covers row blocks 2*t128 (waves 0,1) and 2*t128+1 (waves 2,3)
-      for (int half = 0; half < 2; ++half) {
-        const int R = 2 * t128 + half;
-        if (R >= p.nb) break;
-        uint32_t *kept = half ? kept1 : kept0;
-        const int e0 = max(rp[R], 0), e1 = min(rp[R + 1], p.cap_b);
-        for (int e = e0 + tid; e < e1; e += 256) {
-          const int C = bc[e];
-          if (C >= 0 && C <= R) {
-            atomicOr(&need[C >> 5], 1u << (C & 31));
-            atomicOr(&kept[C >> 5], 1u << (C & 31));
-          }
-        }
+    const int tpb = p.b / BK;  // key tiles per key block: their bits are adjacent in one word
+    const uint32_t tbits = tpb == 2 ? 3u : 1u;
+    for (int e = tid; e < na + nbk; e += 256) {
+      const bool second = e >= na;
+      const int C = bc[second ? eb0 + (e - na) : ea0 + e];
+      if (C >= 0 && C <= Ra + (second ? 1 : 0)) {
+        const int kt = C * tpb;
+        atomicOr(&need[kt >> 5], tbits << (kt & 31));
+        if (!second) atomicOr(&kept0[kt >> 5], tbits << (kt & 31));
+        if (second || p.b == BQ) atomicOr(&kept1[kt >> 5], tbits << (kt & 31));
       }
     }
   }
@@ -279,7 +284,6 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
   const uint16_t *__restrict__ Vh = p.V + (size_t)kvh * p.kv_hs;
   const uint16_t *__restrict__ Kgh = p.Kg + (size_t)h * p.kvg_rows * p.kv_rs;
   const uint16_t *__restrict__ Vgh = p.Vg + (size_t)h * p.kvg_rows * p.kv_rs;
-  const uint32_t *__restrict__ offbm = p.offbits + (size_t)h * (N / 32);
   const uint32_t *__restrict__ colbm = p.colbits + (size_t)h * (N / 32);
 
   f32x16 oacc[4];
@@ -500,6 +504,7 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
   // Nothing here is reused, so the phase lives on memory latency: the reads of the next offset
   // (column-bitmap words, K, V - in that order) are issued as soon as S^T has consumed the K
   // registers, and each wave has two V tiles.
+  if (tid == 0 && home_open) ticket = (int)atomicAdd(&p.queue[home], 1u);  // used at the next item
   if (has_offs) __syncthreads();  // all waves are done with the shared tiles: reuse them as private V tiles
   if (has_offs && r0 < N) {
     const int32_t *__restrict__ offp = p.offs + (size_t)h * p.k_s;
