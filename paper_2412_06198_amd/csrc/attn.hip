@@ -268,12 +268,15 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
     if (lane == 0) s_ntiles = base;
   }
 
-  int cmax = cle;  // gather tiles this wave needs: up to its last query's cut
-  for (int d = 32; d >= 1; d >>= 1) cmax = max(cmax, __shfl_xor(cmax, d));
+  int cmax = cle, cmin = cle;  // gather tiles this wave needs: up to its last query's cut; its first query's cut
+  for (int d = 32; d >= 1; d >>= 1) {
+    cmax = max(cmax, __shfl_xor(cmax, d));
+    cmin = min(cmin, __shfl_xor(cmin, d));
+  }
   if (lane == 0) s_cmax[wv] = cmax;
   __syncthreads();
   const int ntr = __builtin_amdgcn_readfirstlane(s_ntiles);
-  const int cwave = __builtin_amdgcn_readfirstlane(cmax);
+  const int cwave = __builtin_amdgcn_readfirstlane(cmax), cwmin = __builtin_amdgcn_readfirstlane(cmin);
   const int call = __builtin_amdgcn_readfirstlane(max(max(s_cmax[0], s_cmax[1]), max(s_cmax[2], s_cmax[3])));
   const int ng = (call + BK - 1) / BK;
   const int ntot = ntr + ng;
@@ -357,8 +360,11 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
 
     // ---- what this wave keeps of the tile: a 64-bit mask per lane over the key slots ---------
     // slot c (0..59 used) stands for key_local = c + 4*gg; see the accumulator layout below.
-    bool active, needmask;
+    // Without selected columns inside the tile the mask is a threshold (slot c kept iff c <= lim),
+    // applied with one compare per element; km is then only needed by the counted variant.
+    bool active, needmask, bits = false;
     uint64_t km;
+    int lim = 63;
     if (t < ntr) {
       const int kt = __builtin_amdgcn_readfirstlane((int)tlist[t]);
       const int j0 = kt * BK;
@@ -368,18 +374,21 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
       const uint64_t vm = has_cols ? ((uint64_t)uload(colbm, 2 * kt) | ((uint64_t)uload(colbm, 2 * kt + 1) << 32)) : 0ull;
       needmask = !(vm == 0 && j0 + 63 <= r0);
       km = ~0ull;
+      bits = vm != 0;
       if (active && needmask) {
-        const int lim = iq - j0 - 4 * gg;  // causal: slot c kept iff c <= lim
+        lim = iq - j0 - 4 * gg;  // causal: slot c kept iff c <= lim
         const uint64_t cm = lim < 0 ? 0ull : (lim >= 63 ? ~0ull : ((2ull << lim) - 1ull));
         km = cm & ~(vm >> (4 * gg));  // selected columns are served by the gather tiles
       }
     } else {
       const int gi = t - ntr;
-      const int cnt = cle - gi * BK;  // visible columns of this tile for this query
-      const int lim = cnt - 1 - 4 * gg;
-      km = lim < 0 ? 0ull : (lim >= 63 ? ~0ull : ((2ull << lim) - 1ull));
-      needmask = true;
       active = cwave > gi * BK;
+      needmask = cwmin < (gi + 1) * BK;  // some query of the wave sees only a part of this tile
+      km = ~0ull;
+      if (needmask) {
+        lim = cle - gi * BK - 1 - 4 * gg;  // visible columns of this tile for this query, as a slot limit
+        km = lim < 0 ? 0ull : (lim >= 63 ? ~0ull : ((2ull << lim) - 1ull));
+      }
     }
     if (!active) continue;
     if constexpr (STATS) {
@@ -421,13 +430,23 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
       __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
     }
     if (needmask) {
+      if (bits) {
 #pragma unroll
-      for (int hf = 0; hf < 2; ++hf)
+        for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int c = 32 * hf + 8 * (r / 4) + (r % 4);
-          if (!((km >> c) & 1ull)) sacc[hf][r] = -INFINITY;
-        }
+          for (int r = 0; r < 16; ++r) {
+            const int c = 32 * hf + 8 * (r / 4) + (r % 4);
+            if (!((km >> c) & 1ull)) sacc[hf][r] = -INFINITY;
+          }
+      } else {
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int c = 32 * hf + 8 * (r / 4) + (r % 4);
+            if (c > lim) sacc[hf][r] = -INFINITY;
+          }
+      }
     }
     // ---- online softmax (log2 domain) -----------------------------------------------------------
     float tmax = -INFINITY;
