@@ -38,7 +38,9 @@ struct AttnArgs {
   int64_t q_hs, q_rs, kv_hs, kv_rs;
   float c;  // softmax scale * log2(e)
   unsigned int *queue;           // [8] work-queue heads, zeroed by index_bitmaps_kernel
-  int n_items;
+  int n_items;  // (head, row block) items in all
+  int xs;       // queues (XCDs) that share one KV head at a time: 1, 2, 4 or 8
+  int qcap;     // tickets per queue, holes of the id space included
   unsigned long long *counters;  // instrumentation only: {32x32 sub-tiles multiplied, kept (query,key) pairs}
 };
 
@@ -150,17 +152,20 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
   const int wv = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);  // wave-uniform for the compiler too
 
   // Persistent workgroups pull (head, row block) items from eight queues, one per XCD
-  // (consecutive workgroup ids land on consecutive XCDs): item id = queue + 8*k.  KV heads
-  // rotate fastest in the item id, so a queue - and with it an XCD and its L2 - stays on one
-  // KV head while Hkv is a multiple of 8.  The longest (last) row blocks come first.  A
+  // (consecutive workgroup ids land on consecutive XCDs).  xs queues share one KV head at a time
+  // and 8/xs KV heads are in progress together: with xs = 1 a KV head lives in a single L2, with
+  // larger xs fewer KV heads are live at once, so that the rows the diagonal phase fetches (no
+  // reuse inside an L2) come out of the memory-side cache instead of HBM.  Ticket k of queue qn:
+  // phase k / per_q selects the KV head, the rest walks the row blocks qn % xs, qn % xs + xs, ...
+  // from the last (longest) one down, the g query heads of a row block side by side.  A
   // workgroup whose own queue is empty takes from the others, then exits.  The ticket for the
   // next item of the home queue is drawn while the current item finishes, so its round trip is
   // off the critical path.
   __shared__ int s_item;
   const int home = blockIdx.x & 7;
-  int ticket = 0;         // thread 0 only: position drawn from the home queue
-  bool home_open = true;  // thread 0 only: the home queue still had items at the last draw
-  if (threadIdx.x == 0) ticket = (int)atomicAdd(&p.queue[home], 1u);
+  int ticket = 0;            // thread 0 only: position drawn from the home queue
+  bool have_ticket = false;  // thread 0 only: ticket was drawn ahead and is not used yet
+  bool home_open = true;     // thread 0 only: the home queue still had items at the last draw
   for (;;) {
   // Lane-derived constants are recomputed per item from an opaque copy of the thread id:
   // hoisted out of this loop they would stay live across every phase and spill.
@@ -171,25 +176,35 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
   if (tid == 0) {
     int item = -1;
     if (home_open) {
-      if (home + 8 * ticket < p.n_items) item = home + 8 * ticket;
+      if (!have_ticket) ticket = (int)atomicAdd(&p.queue[home], 1u);
+      have_ticket = false;
+      if (ticket < p.qcap) item = home + 8 * ticket;
       else home_open = false;
     }
     for (int qq = 1; qq < 8 && item < 0; ++qq) {
       const int qn = (home + qq) & 7;
-      if (qn + 8 * (int)__hip_atomic_load(&p.queue[qn], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= p.n_items)
+      if ((int)__hip_atomic_load(&p.queue[qn], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= p.qcap)
         continue;
       const int k = (int)atomicAdd(&p.queue[qn], 1u);
-      if (qn + 8 * k < p.n_items) item = qn + 8 * k;
+      if (k < p.qcap) item = qn + 8 * k;
     }
     s_item = item;
   }
   __syncthreads();
   const int id = __builtin_amdgcn_readfirstlane(s_item);
   if (id < 0) break;
-  const int kvh = id % p.Hkv;
-  const int rest = id / p.Hkv;
-  const int h = kvh * p.g + rest % p.g;
-  const int t128 = p.nT - 1 - rest / p.g;
+  int kvh, h, t128;
+  {
+    const int qn = id & 7, k = id >> 3;
+    const int nslots = 8 / p.xs, slot = qn / p.xs, sub = qn % p.xs;
+    const int per_q = (p.nT + p.xs - 1) / p.xs * p.g;
+    const int r = k % per_q;
+    const int tidx = r / p.g * p.xs + sub;
+    kvh = k / per_q * nslots + slot;
+    if (kvh >= p.Hkv || tidx >= p.nT) continue;  // a hole of the id space
+    h = kvh * p.g + r % p.g;
+    t128 = p.nT - 1 - tidx;
+  }
   const int i0 = t128 * BQ;
   const int r0 = i0 + 32 * wv;
   const int iq = r0 + q;  // this lane's query row
@@ -523,7 +538,10 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
   // Nothing here is reused, so the phase lives on memory latency: the reads of the next offset
   // (column-bitmap words, K, V - in that order) are issued as soon as S^T has consumed the K
   // registers, and each wave has two V tiles.
-  if (tid == 0 && home_open) ticket = (int)atomicAdd(&p.queue[home], 1u);  // used at the next item
+  if (tid == 0 && home_open) {  // used at the next item
+    ticket = (int)atomicAdd(&p.queue[home], 1u);
+    have_ticket = true;
+  }
   if (has_offs) __syncthreads();  // all waves are done with the shared tiles: reuse them as private V tiles
   if (has_offs && r0 < N) {
     const int32_t *__restrict__ offp = p.offs + (size_t)h * p.k_s;
@@ -698,6 +716,12 @@ hipError_t launch_sparse_prefill(const Shape &sh, const Workspace &ws, const uin
   gather_columns_kernel<<<dim3(a.kvg_rows / BK, sh.Hq), 256, 0, st>>>(a);
   a.queue = ws.queue;
   a.n_items = a.nT * sh.Hq;
+  // KV heads in progress together: as many as there are queues, unless their K and V rows
+  // (what the diagonal phase streams) exceed the 256 MiB memory-side cache
+  a.xs = 1;
+  while (a.xs < 8 && 8 / a.xs > sh.Hkv) a.xs *= 2;  // fewer than 8 KV heads: no idle queues
+  while (a.xs < 8 && (size_t)(8 / a.xs) * sh.N * kHeadDim * 2 * 2 > ((size_t)256 << 20)) a.xs *= 2;
+  a.qcap = (a.nT + a.xs - 1) / a.xs * sh.g * ((sh.Hkv + 8 / a.xs - 1) / (8 / a.xs));
   const int grid = a.n_items < 2 * sh.n_cu ? a.n_items : 2 * sh.n_cu;  // two resident workgroups per CU
   if (counters)
     sparse_prefill_kernel<true><<<grid, 256, 0, st>>>(a);
