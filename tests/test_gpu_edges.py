@@ -123,3 +123,24 @@ def test_empty_index_parts():
     torch.cuda.synchronize()
     ref, _, _ = orc.masked_rows(Q, K, V, b, ix)
     check_attention(host_f64(Od), ref, "diagonal blocks only")
+
+
+@pytest.mark.parametrize("Hq,Hkv,N,b", [(3, 3, 704, 64), (10, 5, 640, 128), (6, 1, 576, 64),
+                                        (16, 16, 384, 128), (12, 6, 1088, 64)])
+def test_head_counts_off_the_queue_grid(Hq, Hkv, N, b):
+    # KV head counts that do not divide the eight work queues (and row-block counts that do not
+    # divide the queues of a KV head): every (head, row block) must still be computed exactly once
+    print(f"case heads Hq={Hq} Hkv={Hkv} N={N} b={b}", flush=True)
+    w = 64
+    Q, K, V = gen.random_qkv(Hq, Hkv, N, 128, seed=100 + Hq)
+    bud = orc.default_budgets(N, b, 0.3)
+    ses = make_session(Hq, Hkv, N, b, w, bud)
+    Qd, Kd, Vd = dev_bf16(Q), dev_bf16(K), dev_bf16(V)
+    Od = torch.full_like(Qd, 7.0)
+    ov = [h % 3 for h in range(Hq)]
+    _run_all(ses, Qd, Kd, Vd, Od, ov)
+    ix = download_index(ses)
+    v, s, blk = download_scores(ses)
+    assert_index_equal(ix, orc.build_index(v, s, blk, N, b, w, bud, override=ov))
+    ref, _, _ = orc.masked_rows(Q, K, V, b, ix)
+    check_attention(host_f64(Od), ref, f"heads {Hq}/{Hkv}")
