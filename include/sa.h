@@ -139,6 +139,35 @@ sa_status sa_sparse_prefill_counted(sa_ctx *ctx, const void *Q, const void *K, c
                                     sa_index idx, void *O, uint64_t *counters_dev,
                                     void *hip_stream);
 
+/* Offline pattern search, "Kernel-Aware Sparse Pattern Search Algorithm" (Alg. 1), one head at a
+ * time.  Candidates: the three patterns, each with one integer size (its search space):
+ *   SA_TRIANGULAR      local_blocks = x,                       1 <= x <= nb
+ *   SA_INTERVAL_SLASH  k_slash = x, k_vertical = min(N, 32 x), 1 <= x <= max(1, N/32)
+ *   SA_BLOCK_CLUSTER   k_blocks = x,                           nb <= x <= nb (nb+1)/2
+ * (sink_blocks, block, last_q, scale and strides come from ctx's config).  FLOPs of a candidate =
+ * 4 * head_dim * kept (query, key) pairs of the index built from it, so the target and the
+ * tolerance are given in pairs.  RefineSearchSpace: bisection on x; it stops at the first probe
+ * within eps_pairs of target_pairs, else takes of the two adjacent sizes around the target the
+ * closer one (the smaller on a tie).  Evaluate Patterns: Frobenius norm of (sparse output - dense
+ * causal output) of the head for every refined candidate; `pattern` is the smallest (ties: lowest
+ * id), ready for sa_build_index's pattern_override.
+ * Q, K, V, scores: device, as for the other calls (scores from sa_estimate_patterns).  scratch:
+ * DEVICE, 256-byte aligned, sa_search_scratch_bytes bytes, owned by the caller.  out_host: HOST
+ * array of n_q_heads results, candidates in pattern-id order.  The call runs the index builder and
+ * the attention kernel of this library on one-head contexts it creates and destroys, waits for the
+ * stream after every probe (do not capture it in a graph) and returns when all results are in
+ * out_host.  ctx's own workspace is not used. */
+typedef struct {
+  int32_t pattern;   /* argmin of err */
+  int32_t param[3];  /* refined size x of each candidate */
+  int64_t pairs[3];  /* kept (query, key) pairs at that size */
+  double err[3];     /* || O_sparse - O_dense ||_F at that size */
+} sa_search_head;
+sa_status sa_search_scratch_bytes(const sa_ctx *ctx, size_t *bytes);
+sa_status sa_search_patterns(sa_ctx *ctx, const void *Q, const void *K, const void *V, sa_scores scores,
+                             int64_t target_pairs, int64_t eps_pairs, void *scratch_dev,
+                             size_t scratch_bytes, sa_search_head *out_host, void *hip_stream);
+
 const char *sa_last_error(const sa_ctx *ctx);
 
 /* Library version string. */

@@ -71,9 +71,13 @@ def library():
         lib.sa_build_index.argtypes = [vp, SaScores, C.POINTER(C.c_int32), SaIndex, vp]
         lib.sa_sparse_prefill.argtypes = [vp, vp, vp, vp, SaIndex, vp, vp]
         lib.sa_sparse_prefill_counted.argtypes = [vp, vp, vp, vp, SaIndex, vp, vp, vp]
+        lib.sa_search_scratch_bytes.argtypes = [vp, C.POINTER(C.c_size_t)]
+        lib.sa_search_patterns.argtypes = [vp, vp, vp, vp, SaScores, C.c_int64, C.c_int64, vp, C.c_size_t,
+                                           C.POINTER(SaSearchHead), vp]
         for f in ("sa_default_budgets", "sa_create", "sa_scores_bytes", "sa_index_bytes",
                   "sa_workspace_bytes", "sa_set_workspace", "sa_estimate_patterns",
-                  "sa_build_index", "sa_sparse_prefill", "sa_sparse_prefill_counted"):
+                  "sa_build_index", "sa_sparse_prefill", "sa_sparse_prefill_counted",
+                  "sa_search_scratch_bytes", "sa_search_patterns"):
             getattr(lib, f).restype = st
         _lib = lib
     return _lib
@@ -157,6 +161,27 @@ def sa_sparse_prefill_counted(ctx, Q, K, V, index: SaIndex, O, counters, stream=
                                                _ptr(counters), stream), ctx)
 
 
+class SaSearchHead(C.Structure):
+    _fields_ = [("pattern", C.c_int32), ("param", C.c_int32 * 3), ("pairs", C.c_int64 * 3),
+                ("err", C.c_double * 3)]
+
+
+def sa_search_scratch_bytes(ctx) -> int:
+    out = C.c_size_t()
+    _check(library().sa_search_scratch_bytes(ctx, C.byref(out)), ctx)
+    return out.value
+
+
+def sa_search_patterns(ctx, Q, K, V, scores: SaScores, target_pairs, eps_pairs, scratch, scratch_bytes,
+                       n_heads, stream=None):
+    out = (SaSearchHead * n_heads)()
+    _check(library().sa_search_patterns(ctx, _ptr(Q), _ptr(K), _ptr(V), scores, C.c_int64(int(target_pairs)),
+                                        C.c_int64(int(eps_pairs)), _ptr(scratch), C.c_size_t(scratch_bytes),
+                                        out, stream), ctx)
+    return [{"pattern": int(r.pattern), "param": list(r.param), "pairs": list(r.pairs), "err": list(r.err)}
+            for r in out]
+
+
 class Session:
     """Owns a context plus the torch-allocated score / index / workspace buffers of one shape."""
 
@@ -225,6 +250,14 @@ class Session:
         sa_sparse_prefill_counted(self.ctx, Q, K, V, self.index(), O, cnt, self.stream())
         self.torch.cuda.synchronize(self.device)
         return [int(x) for x in cnt.cpu()]
+
+    def search_patterns(self, Q, K, V, target_pairs, eps_pairs):
+        """Alg. 1 on the scores of the last estimate(): one dict per head."""
+        nbytes = sa_search_scratch_bytes(self.ctx)
+        scratch = self.torch.empty(nbytes + 256, dtype=self.torch.uint8, device=self.device)
+        off = (-scratch.data_ptr()) % 256
+        return sa_search_patterns(self.ctx, Q, K, V, self.scores(), target_pairs, eps_pairs,
+                                  scratch.data_ptr() + off, nbytes, self.cfg.n_q_heads, self.stream())
 
     def close(self):
         if self.ctx is not None:

@@ -7,17 +7,6 @@
 
 #include "sa_internal.h"
 
-struct sa_ctx {
-  sa_config cfg;
-  sa::Shape sh;
-  sa::Workspace ws;
-  sa::Fork fork;
-  bool have_ws;
-  size_t ws_bytes;
-  size_t off[11];
-  char err[256];
-};
-
 namespace {
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }

@@ -44,6 +44,22 @@ size_t index_scratch_bytes(int n_heads);
 // everything is enqueued on the caller's stream.
 struct Fork { hipStream_t aux; hipEvent_t fork, mid, join; };
 
+}  // namespace sa
+
+// The context behind the opaque handle of the C ABI (host memory).
+struct sa_ctx {
+  sa_config cfg;
+  sa::Shape sh;
+  sa::Workspace ws;
+  sa::Fork fork;
+  bool have_ws;
+  size_t ws_bytes;
+  size_t off[11];
+  char err[256];
+};
+
+namespace sa {
+
 hipError_t launch_estimate(const Shape &sh, const Workspace &ws, const uint16_t *Q,
                            const uint16_t *K, sa_scores out, hipStream_t st, const Fork &fk);
 hipError_t launch_build_index(const Shape &sh, const Workspace &ws, sa_scores in,
