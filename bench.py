@@ -227,6 +227,57 @@ def run_sweep(steps):
                                "planted mix 25/50/25", "rows": rows}))
 
 
+def run_search(N, with_cpu):
+    """Offline pattern search (Kernel-Aware Sparse Pattern Search Algorithm, Alg. 1) on one GQA
+    group (planted Triangular, Interval-Slash, Interval-Slash, Block-Cluster heads): seconds per
+    head, what it chose, and the oracle of the same search timed on a small head beside it."""
+    import numpy as np
+    import torch
+
+    import paper_2412_06198_amd as sa
+    from harness import gen
+
+    def up(bits):
+        return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).cuda()
+
+    b = 64 if N <= 32768 else 128
+    wl = gen.scaled(gen.WORKLOADS["cfg3"], name=f"search{N}", seq_len=N, block=b, n_q_heads=4, n_kv_heads=1,
+                    hot_block=b, seed=8000 + N)
+    data = gen.generate(wl)
+    Q, K, V = up(data["Q"]), up(data["K"]), up(data["V"])
+    ses = sa.Session(4, 1, N, b, wl.last_q, keep=wl.keep)
+    ses.estimate(Q, K)
+    torch.cuda.synchronize()
+    target = int(N * (N + 1) // 2 * wl.keep)
+    eps = target // 100
+    ses.search_patterns(Q, K, V, target, eps)          # warm-up
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    res = ses.search_patterns(Q, K, V, target, eps)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    out = {"search": f"Alg. 1 on one GQA group, N={N} block={b}, target {wl.keep} of the causal pairs +-1%",
+           "seconds_per_head": round(dt / 4, 4), "planted": [int(pl.pattern) for pl in data["plants"]],
+           "chosen": [r["pattern"] for r in res], "param": [r["param"] for r in res],
+           "pairs_over_target": [[round(x / target, 4) for x in r["pairs"]] for r in res],
+           "err": [[round(x, 3) for x in r["err"]] for r in res]}
+    log(f"[search] N={N}: {dt / 4:.3f} s per head, planted {out['planted']} chosen {out['chosen']}")
+    ses.close()
+    if with_cpu:
+        from oracle import oracle as orc
+        from oracle import search as osr
+        n = 2048
+        wls = gen.scaled(wl, seq_len=n, block=64, n_q_heads=1, window=min(wl.window, 256), hot_block=64)
+        ds = gen.generate(wls)
+        v, s_, blk = [x.astype(np.float32) for x in orc.estimate(ds["Q"], ds["K"], 64, wls.last_q)]
+        tg = int(n * (n + 1) // 2 * 0.2)
+        t0 = time.perf_counter()
+        osr.search_patterns(ds["Q"], ds["K"], ds["V"], v, s_, blk, 64, wls.last_q, 1, tg, tg // 100)
+        out["cpu_baseline"] = {"value": round(time.perf_counter() - t0, 3), "unit": "s per head", "cores": orc.num_threads(),
+                               "kind": "oracle", "sample": f"fp64 oracle of the same search on one head of {n} tokens"}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -242,6 +293,8 @@ def main():
                     help="only run a plain 1 GiB device copy a few times (reference for HBM byte counters)")
     ap.add_argument("--sweep", action="store_true",
                     help="dense-vs-sparse time per layer from 4K to 128K tokens instead of the benchmark line")
+    ap.add_argument("--search", type=int, default=0, metavar="N",
+                    help="time the offline pattern search (Alg. 1) on one GQA group of N tokens instead")
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (heads shard without communication; "
@@ -264,6 +317,9 @@ def main():
     sa.library()
     if a.sweep:
         run_sweep(a.steps)
+        return
+    if a.search:
+        run_search(a.search, not a.no_cpu_baseline)
         return
     main_res = run_workload(a.workload, a.steps, a.warmup, a.layers, not a.no_cpu_baseline, a.sample_rows)
     also = None

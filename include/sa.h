@@ -134,7 +134,7 @@ sa_status sa_sparse_prefill(sa_ctx *ctx, const void *Q, const void *K, const voi
  * counts 2, a selected diagonal of one wave counts 1; 4*head_dim*32*32 FLOP
  * each) and to counters_dev[1] the number of kept (query, key) pairs, |M| of the sparse
  * softmax of Alg. 2 / Alg. 3.  counters_dev: DEVICE uint64[2], zeroed by the
- * caller.  Slower than sa_sparse_prefill (atomics); never time it. */
+ * caller.  A benchmark times sa_sparse_prefill, not this variant. */
 sa_status sa_sparse_prefill_counted(sa_ctx *ctx, const void *Q, const void *K, const void *V,
                                     sa_index idx, void *O, uint64_t *counters_dev,
                                     void *hip_stream);

@@ -310,6 +310,7 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
+  unsigned st_kept = 0u, st_tiles = 0u;  // counted variant: this lane's kept pairs, this wave's sub-tiles
 
   // ---- global -> LDS pipeline -----------------------------------------------------------------
   // K and V tiles go straight from global memory into LDS (global_load_lds_dwordx4: 16 bytes per
@@ -408,12 +409,8 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
     if (!active) continue;
     if constexpr (STATS) {
       // slots this lane owns: c = 32hf + 8(r/4) + r%4
-      unsigned long long kept = iq < N ? (unsigned long long)__popcll(km & 0x0F0F0F0F0F0F0F0Full) : 0ull;
-      for (int d = 32; d >= 1; d >>= 1) kept += __shfl_xor(kept, d);
-      if (lane == 0) {
-        atomicAdd(&p.counters[0], 2ull);
-        atomicAdd(&p.counters[1], kept);
-      }
+      st_kept += iq < N ? (unsigned)__popcll(km & 0x0F0F0F0F0F0F0F0Full) : 0u;
+      st_tiles += 2u;
     }
 
     // ---- S^T = K Q^T : lane = query (q), accumulator r of half hf <-> key 32hf + 8(r/4) + 4gg + r%4
@@ -622,12 +619,8 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
         if (has_cols && cbit) valid = false;
       }
       if constexpr (STATS) {
-        unsigned long long kept_n = valid ? 1ull : 0ull;
-        for (int d = 32; d >= 1; d >>= 1) kept_n += __shfl_xor(kept_n, d);
-        if (lane == 0) {
-          atomicAdd(&p.counters[0], 1ull);
-          atomicAdd(&p.counters[1], kept_n);
-        }
+        st_kept += valid ? 1u : 0u;
+        st_tiles += 1u;
       }
       float sm = valid ? sv : -INFINITY;
       sm = fmaxf(sm, __shfl_xor(sm, 32));  // both lanes of the pair know the row's score
@@ -646,8 +639,8 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
       l_run += pv;
       const __bf16 pvb = (__bf16)pv, zb = (__bf16)0.f;
       // V of this offset has landed once only the 16 reads of the next offset, all issued after
-      // it, are outstanding (the counted variant also has atomics in flight: wait for everything)
-      if (!STATS && e + 1 < nd) __builtin_amdgcn_s_waitcnt(0x4F70);  // vmcnt(16)
+      // it, are outstanding
+      if (e + 1 < nd) __builtin_amdgcn_s_waitcnt(0x4F70);  // vmcnt(16)
       else __builtin_amdgcn_s_waitcnt(0x0F70);                       // vmcnt(0)
       const uint16_t *Vw = Vw0 + (e & 1) * (32 * 128);
       // P^T is diagonal: slot e2 of k-step u is register 8u+e2
@@ -669,6 +662,14 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
 #undef SA_DIAG_ISSUE
   }
 
+  if constexpr (STATS) {  // one pair of atomics per wave and item
+    unsigned long long kept_n = st_kept;
+    for (int d = 32; d >= 1; d >>= 1) kept_n += __shfl_xor(kept_n, d);
+    if (lane == 0) {
+      atomicAdd(&p.counters[0], (unsigned long long)st_tiles);
+      atomicAdd(&p.counters[1], kept_n);
+    }
+  }
   // ---- epilogue: O[iq][32db + 8(r/4) + 4gg + r%4] = oacc / l -------------------------------------
   const float ltot = l_run + __shfl_xor(l_run, 32);
   const float inv = ltot > 0.f ? 1.f / ltot : 0.f;
