@@ -139,6 +139,17 @@ sa_status sa_sparse_prefill_counted(sa_ctx *ctx, const void *Q, const void *K, c
                                     sa_index idx, void *O, uint64_t *counters_dev,
                                     void *hip_stream);
 
+/* One decode step over the prefill index (Abstract / Introduction: gains "in the decoding phase";
+ * Proposed Method: decode queries are [B, 1, H]; the paper gives no method, this is a reading).
+ * The prompt of seq_len = N tokens was prefilled with idx.  The query at position pos >= N attends,
+ * per query head, the union of: the generated keys N..pos (itself included), the selected columns,
+ * the keys pos - o of the selected diagonal offsets o, and the keys of the key blocks idx keeps for
+ * the last row block of the prompt - each key once - with the prefill's scaled softmax.
+ * q, o [Hq][128] bf16 device, contiguous; K, V as in the prefill (same strides) but holding rows
+ * 0..pos, so kv_head_stride must leave room for them; pos < N + 2^20.  Uses ctx's workspace. */
+sa_status sa_sparse_decode(sa_ctx *ctx, const void *q, const void *K, const void *V, sa_index idx,
+                           int64_t pos, void *o, void *hip_stream);
+
 /* Offline pattern search, "Kernel-Aware Sparse Pattern Search Algorithm" (Alg. 1), one head at a
  * time.  Candidates: the three patterns, each with one integer size (its search space):
  *   SA_TRIANGULAR      local_blocks = x,                       1 <= x <= nb

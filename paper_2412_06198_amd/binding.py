@@ -71,13 +71,14 @@ def library():
         lib.sa_build_index.argtypes = [vp, SaScores, C.POINTER(C.c_int32), SaIndex, vp]
         lib.sa_sparse_prefill.argtypes = [vp, vp, vp, vp, SaIndex, vp, vp]
         lib.sa_sparse_prefill_counted.argtypes = [vp, vp, vp, vp, SaIndex, vp, vp, vp]
+        lib.sa_sparse_decode.argtypes = [vp, vp, vp, vp, SaIndex, C.c_int64, vp, vp]
         lib.sa_search_scratch_bytes.argtypes = [vp, C.POINTER(C.c_size_t)]
         lib.sa_search_patterns.argtypes = [vp, vp, vp, vp, SaScores, C.c_int64, C.c_int64, vp, C.c_size_t,
                                            C.POINTER(SaSearchHead), vp]
         for f in ("sa_default_budgets", "sa_create", "sa_scores_bytes", "sa_index_bytes",
                   "sa_workspace_bytes", "sa_set_workspace", "sa_estimate_patterns",
                   "sa_build_index", "sa_sparse_prefill", "sa_sparse_prefill_counted",
-                  "sa_search_scratch_bytes", "sa_search_patterns"):
+                  "sa_search_scratch_bytes", "sa_search_patterns", "sa_sparse_decode"):
             getattr(lib, f).restype = st
         _lib = lib
     return _lib
@@ -159,6 +160,10 @@ def sa_sparse_prefill(ctx, Q, K, V, index: SaIndex, O, stream=None):
 def sa_sparse_prefill_counted(ctx, Q, K, V, index: SaIndex, O, counters, stream=None):
     _check(library().sa_sparse_prefill_counted(ctx, _ptr(Q), _ptr(K), _ptr(V), index, _ptr(O),
                                                _ptr(counters), stream), ctx)
+
+
+def sa_sparse_decode(ctx, q, K, V, index: SaIndex, pos, o, stream=None):
+    _check(library().sa_sparse_decode(ctx, _ptr(q), _ptr(K), _ptr(V), index, C.c_int64(int(pos)), _ptr(o), stream), ctx)
 
 
 class SaSearchHead(C.Structure):
@@ -250,6 +255,10 @@ class Session:
         sa_sparse_prefill_counted(self.ctx, Q, K, V, self.index(), O, cnt, self.stream())
         self.torch.cuda.synchronize(self.device)
         return [int(x) for x in cnt.cpu()]
+
+    def decode(self, q, K, V, pos, o):
+        """One decode step at position pos >= seq_len over the current index."""
+        sa_sparse_decode(self.ctx, q, K, V, self.index(), pos, o, self.stream())
 
     def search_patterns(self, Q, K, V, target_pairs, eps_pairs):
         """Alg. 1 on the scores of the last estimate(): one dict per head."""

@@ -40,6 +40,7 @@ void carve(sa_ctx *c) {
   c->off[8] = o; o += 256;
   c->off[9] = o; o += align256(sa::index_scratch_bytes(s.Hq));
   c->off[10] = o; o += align256((size_t)s.Hq * (s.N / 32) * 4);
+  c->off[11] = o; o += align256(sa::decode_partial_bytes(s));
   c->ws_bytes = o;
 }
 
@@ -207,6 +208,7 @@ sa_status sa_set_workspace(sa_ctx *c, void *dev, size_t bytes) {
   c->ws.queue = (unsigned int *)(p + c->off[8]);
   c->ws.idx = (void *)(p + c->off[9]);
   c->ws.colprefix = (int32_t *)(p + c->off[10]);
+  c->ws.dec_part = (float *)(p + c->off[11]);
   c->have_ws = true;
   return SA_OK;
 }
@@ -269,6 +271,22 @@ sa_status sa_sparse_prefill_counted(sa_ctx *c, const void *Q, const void *K, con
   if (c && (!counters_dev || ((uintptr_t)counters_dev & 7)))
     return fail(c, SA_ERR_INVALID_ARG, "counters must be an 8-byte aligned device pointer");
   return prefill_common(c, Q, K, V, idx, O, counters_dev, stream);
+}
+
+sa_status sa_sparse_decode(sa_ctx *c, const void *q, const void *K, const void *V, sa_index idx,
+                           int64_t pos, void *o, void *stream) {
+  if (!c) return SA_ERR_INVALID_ARG;
+  if (!q || !K || !V || !o || !idx.n_cols || !idx.cols || !idx.n_offs || !idx.offs || !idx.rowptr ||
+      !idx.blkcols)
+    return fail(c, SA_ERR_INVALID_ARG, "null pointer");
+  if (((uintptr_t)q | (uintptr_t)K | (uintptr_t)V) & 15)
+    return fail(c, SA_ERR_INVALID_ARG, "q, K, V must be 16-byte aligned");
+  if (pos < c->sh.N || pos - c->sh.N >= (1 << 20))
+    return fail(c, SA_ERR_INVALID_ARG, "pos must lie in [seq_len, seq_len + 2^20)");
+  if (!c->have_ws) return fail(c, SA_ERR_INVALID_ARG, "no workspace attached");
+  return hip_result(c, sa::launch_sparse_decode(c->sh, c->ws, (const uint16_t *)q, (const uint16_t *)K,
+                                                (const uint16_t *)V, idx, (int)pos, (uint16_t *)o,
+                                                (hipStream_t)stream));
 }
 
 const char *sa_last_error(const sa_ctx *c) { return c ? c->err : "null context"; }

@@ -32,6 +32,7 @@ struct Workspace {
   float2 *stats;                  // [Hq][64] (max * scale*log2e, 1/sum)
   uint32_t *offbits, *colbits;    // [Hq][N/32] membership bitmaps of offs / cols
   int32_t *colprefix;             // [Hq][N/32] number of selected columns before each word of colbits
+  float *dec_part;                // [Hq][splits][132] partial (max, sum, output) of the decode step
   unsigned int *queue;            // [8] work-queue heads of the attention kernel
   void *idx;                      // per-head scratch of the index builder
   uint16_t *kg, *vg;              // [Hq][roundup64(k_v)][kv_rs] gathered K / V rows of the selected columns
@@ -54,7 +55,7 @@ struct sa_ctx {
   sa::Fork fork;
   bool have_ws;
   size_t ws_bytes;
-  size_t off[11];
+  size_t off[12];
   char err[256];
 };
 
@@ -64,6 +65,9 @@ hipError_t launch_estimate(const Shape &sh, const Workspace &ws, const uint16_t 
                            const uint16_t *K, sa_scores out, hipStream_t st, const Fork &fk);
 hipError_t launch_build_index(const Shape &sh, const Workspace &ws, sa_scores in,
                               const Override &ov, sa_index out, hipStream_t st);
+size_t decode_partial_bytes(const Shape &sh);
+hipError_t launch_sparse_decode(const Shape &sh, const Workspace &ws, const uint16_t *q, const uint16_t *K,
+                                const uint16_t *V, sa_index idx, int pos, uint16_t *o, hipStream_t st);
 hipError_t launch_sparse_prefill(const Shape &sh, const Workspace &ws, const uint16_t *Q,
                                  const uint16_t *K, const uint16_t *V, sa_index idx, uint16_t *O,
                                  unsigned long long *counters, hipStream_t st);
