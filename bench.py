@@ -278,6 +278,57 @@ def run_search(N, with_cpu):
     print(json.dumps(out))
 
 
+def run_decode(name, steps):
+    """One decode step over the prefill index of a benchmark workload (the query of the next
+    token): microseconds per step for all heads and the HBM rate on the K and V rows it lists."""
+    import numpy as np
+    import torch
+
+    import paper_2412_06198_amd as sa
+    from harness import gen
+
+    def up(bits):
+        return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).cuda()
+
+    wl = gen.WORKLOADS[name]
+    data = gen.generate(wl)
+    Hq, Hkv, N, b, d = wl.n_q_heads, wl.n_kv_heads, wl.seq_len, wl.block, wl.head_dim
+    pad = 64                                   # room for generated keys behind the prompt
+    Q = up(data["Q"])
+    K = torch.zeros((Hkv, N + pad, d), dtype=torch.bfloat16, device="cuda")
+    V = torch.zeros_like(K)
+    K[:, :N], V[:, :N] = up(data["K"]), up(data["V"])
+    K[:, N:], V[:, N:] = K[:, :pad], V[:, :pad]   # stand-ins for the generated tokens' keys and values
+    ses = sa.Session(Hq, Hkv, N, b, wl.last_q, keep=wl.keep, kv_head_stride=(N + pad) * d)
+    ses.estimate(Q, K)
+    ses.build_index(None)
+    q = Q[:, N - 1].contiguous()
+    o = torch.empty_like(q)
+    pos = N + 7
+    for _ in range(3):
+        ses.decode(q, K, V, pos, o)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        ses.decode(q, K, V, pos, o)
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) / steps * 1e3
+    nb = N // b
+    listed = ((ses.rowptr[:, nb] - ses.rowptr[:, nb - 1]).clamp(min=0) * b + ses.n_cols.clamp(min=0) +
+              ses.n_offs.clamp(min=0) + (pos - N + 1)).sum().item()
+    byt = listed * 2 * d * 2
+    out = {"decode": f"one decode step over the prefill index, {name}: Hq={Hq} Hkv={Hkv} N={N} block={b} keep={wl.keep}",
+           "us_per_step": round(us, 2), "listed_keys_all_heads": int(listed),
+           "roofline": {"bound": "hbm", "kernel": "decode_partial_kernel", "achieved": round(byt / us / 1e3, 1),
+                        "peak": 8000.0, "unit": "GB/s", "frac": round(byt / us / 1e3 / 8000.0, 4), "traffic": None},
+           "note": "bytes = K and V rows of the listed keys (before the union drops repeats); two launches per step"}
+    log(f"[decode] {name}: {us:.1f} us per step, {listed} keys listed, {byt / us / 1e3:.0f} GB/s")
+    ses.close()
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -295,6 +346,8 @@ def main():
                     help="dense-vs-sparse time per layer from 4K to 128K tokens instead of the benchmark line")
     ap.add_argument("--search", type=int, default=0, metavar="N",
                     help="time the offline pattern search (Alg. 1) on one GQA group of N tokens instead")
+    ap.add_argument("--decode", action="store_true",
+                    help="time one decode step over the prefill index of --workload instead")
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (heads shard without communication; "
@@ -317,6 +370,9 @@ def main():
     sa.library()
     if a.sweep:
         run_sweep(a.steps)
+        return
+    if a.decode:
+        run_decode(a.workload, max(a.steps, 50))
         return
     if a.search:
         run_search(a.search, not a.no_cpu_baseline)

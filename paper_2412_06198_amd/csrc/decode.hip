@@ -47,17 +47,20 @@ __global__ __launch_bounds__(256) void decode_partial_kernel(DecArgs p) {
   const int nblk = e1 - e0;
   const int nc = min(max(p.n_cols[h], 0), p.k_v), no = min(max(p.n_offs[h], 0), p.k_s);
   const int ns = p.pos - N + 1;
+  const bool need_cols = no > 0 && nc > 0;  // the column bitmap only screens diagonal keys
   for (int i = tid; i < (nb + 31) / 32; i += 256) blkbm[i] = 0u;
-  for (int i = tid; i < N / 32; i += 256) colbm[i] = 0u;
+  if (need_cols)
+    for (int i = tid; i < N / 32; i += 256) colbm[i] = 0u;
   __syncthreads();
   for (int e = tid; e < nblk; e += 256) {
     const int C = bc[e0 + e];
     if (C >= 0 && C < nb) atomicOr(&blkbm[C >> 5], 1u << (C & 31));
   }
-  for (int i = tid; i < nc; i += 256) {
-    const int c = colp[i];
-    if (c >= 0 && c < N) atomicOr(&colbm[c >> 5], 1u << (c & 31));
-  }
+  if (need_cols)
+    for (int i = tid; i < nc; i += 256) {
+      const int c = colp[i];
+      if (c >= 0 && c < N) atomicOr(&colbm[c >> 5], 1u << (c & 31));
+    }
   __syncthreads();
   // the head's key list: block keys, columns, diagonal keys, generated keys; this workgroup's share
   const int n0 = nblk * b, n1 = n0 + nc, n2 = n1 + no, total = n2 + ns;
@@ -85,7 +88,7 @@ __global__ __launch_bounds__(256) void decode_partial_kernel(DecArgs p) {
         const int o = offp[t - n1];
         const int jj = p.pos - o;
         if (o >= 0 && jj >= 0 && jj < N && !((blkbm[(jj / b) >> 5] >> ((jj / b) & 31)) & 1u) &&
-            !((colbm[jj >> 5] >> (jj & 31)) & 1u))
+            !(need_cols && ((colbm[jj >> 5] >> (jj & 31)) & 1u)))
           j = jj;
       } else {
         j = N + (t - n2);
@@ -134,20 +137,29 @@ __global__ __launch_bounds__(256) void decode_partial_kernel(DecArgs p) {
   }
 }
 
-// grid Hq, 128 threads: merge the S partials of a head, normalise, round to bf16.
+// grid Hq, 128 threads: merge the S <= 64 partials of a head, normalise, round to bf16.  The
+// (max, sum) pairs are read by one lane each and all output reads of a thread are independent.
 __global__ __launch_bounds__(kHeadDim) void decode_merge_kernel(DecArgs p) {
+  __shared__ float wgt[64];
+  __shared__ float s_L;
   const int h = blockIdx.x, tid = threadIdx.x;
   const float *src = p.part + (size_t)h * p.S * kPartStride;
-  float M = -INFINITY;
-  for (int k = 0; k < p.S; ++k) M = fmaxf(M, src[(size_t)k * kPartStride]);
-  float L = 0.f, O = 0.f;
-  for (int k = 0; k < p.S; ++k) {
-    const float mk = src[(size_t)k * kPartStride];
-    if (mk == -INFINITY) continue;
-    const float wgt = __builtin_amdgcn_exp2f(mk - M);
-    L += src[(size_t)k * kPartStride + 1] * wgt;
-    O += src[(size_t)k * kPartStride + 4 + tid] * wgt;
+  if (tid < 64) {
+    const float mk = tid < p.S ? src[(size_t)tid * kPartStride] : -INFINITY;
+    const float lk = tid < p.S ? src[(size_t)tid * kPartStride + 1] : 0.f;
+    float M = mk;
+    for (int d = 32; d >= 1; d >>= 1) M = fmaxf(M, __shfl_xor(M, d));
+    const float w = mk == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mk - M);
+    float L = lk * w;
+    for (int d = 32; d >= 1; d >>= 1) L += __shfl_xor(L, d);
+    wgt[tid] = w;
+    if (tid == 0) s_L = L;
   }
+  __syncthreads();
+  float O = 0.f;
+#pragma unroll 8
+  for (int k = 0; k < p.S; ++k) O = __builtin_fmaf(src[(size_t)k * kPartStride + 4 + tid], wgt[k], O);
+  const float L = s_L;
   const __bf16 r = (__bf16)(L > 0.f ? O / L : 0.f);
   p.o[(size_t)h * kHeadDim + tid] = __builtin_bit_cast(uint16_t, r);
 }
@@ -155,7 +167,7 @@ __global__ __launch_bounds__(kHeadDim) void decode_merge_kernel(DecArgs p) {
 }  // namespace
 
 int decode_splits(const Shape &sh) {
-  const int s = 1024 / (sh.Hq > 0 ? sh.Hq : 1);
+  const int s = 512 / (sh.Hq > 0 ? sh.Hq : 1);  // about two workgroups per compute unit in all
   return s < 1 ? 1 : (s > 64 ? 64 : s);
 }
 
