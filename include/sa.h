@@ -8,6 +8,8 @@
  *      columns, diagonals and blocks (sa_build_index),
  *   3. runs causal softmax attention over the selected entries only
  *      (sa_sparse_prefill).
+ * Beside this path: one decode step over the same index (sa_sparse_decode)
+ * and the offline per-head pattern search (sa_search_patterns).
  *
  * Conventions
  *   - C99 types only.  Q, K, V, O are DEVICE pointers to raw bf16 (16-bit)
@@ -15,7 +17,8 @@
  *   - The caller owns every device buffer (Q, K, V, O, scores, index,
  *     workspace).  Sizes come from the *_bytes queries.  The library never
  *     allocates or frees device memory and never synchronises the host: the
- *     three compute calls enqueue kernels on the given HIP stream and return.
+ *     compute calls enqueue kernels on the given HIP stream and return (the
+ *     offline search is the exception: the host steers it, see there).
  *     sa_estimate_patterns runs part of its kernels on a side stream that the
  *     context owns (created by sa_create, default priority); that stream waits
  *     for the given stream at entry and the given stream waits for it at exit,
