@@ -276,7 +276,9 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
       while (wbits) {
         const int bit = __ffs(wbits) - 1;
         wbits &= wbits - 1;
-        tlist[pos++] = (uint16_t)((w0 + lane) * 32 + bit);
+        // entry: key tile (bits 0..11), kept by waves 0,1 (bit 14) / by waves 2,3 (bit 15)
+        tlist[pos++] = (uint16_t)(((w0 + lane) * 32 + bit) | (((kept0[w0 + lane] >> bit) & 1u) << 14) |
+                                  (((kept1[w0 + lane] >> bit) & 1u) << 15));
       }
       base += __shfl(incl, 63);
     }
@@ -327,11 +329,11 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(gptr), \
                "s"(ldsb)                                                                              \
                : "memory")
-#define SA_ISSUE_TILE(t, buf)                                                                    \
+#define SA_ISSUE_TILE(t, buf, ent)                                                                  \
   {                                                                                              \
     const uint16_t *kb, *vb;                                                                     \
     if ((t) < ntr) {                                                                             \
-      const size_t j0_ = (size_t)__builtin_amdgcn_readfirstlane((int)tlist[t]) * BK * p.kv_rs;    \
+      const size_t j0_ = (size_t)((ent) & 0xFFF) * BK * p.kv_rs;                                 \
       kb = Kh + j0_; vb = Vh + j0_;                                                              \
     } else {                                                                                     \
       const size_t g0_ = (size_t)((t) - ntr) * BK * p.kv_rs;                                     \
@@ -364,7 +366,11 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
 #define SA_VTR(tile, db, key0) \
   __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)((const char *)(tile) + ((vbase ^ (unsigned)((db) << 6)) + (key0) * 256)))
 
-  if (ntot > 0) SA_ISSUE_TILE(0, 0);
+  // list entries travel one tile ahead in scalar registers, so that neither the copy of the next
+  // tile nor this tile's keep test waits for an LDS read behind the barrier
+  int e_cur = __builtin_amdgcn_readfirstlane((int)tlist[0]);
+  int r_nxt = (int)tlist[1];  // raw LDS value: made scalar only where it is used, a tile later
+  if (ntot > 0) SA_ISSUE_TILE(0, 0, e_cur);
 
   for (int t = 0; t < ntot; ++t) {
     const int cur = t & 1;
@@ -372,7 +378,11 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
     // whole tile is in LDS[cur] and every wave has finished reading LDS[cur^1] (tile t-1)
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
     __syncthreads();
-    if (t + 1 < ntot) SA_ISSUE_TILE(t + 1, cur ^ 1);
+    const int e_nxt = __builtin_amdgcn_readfirstlane(r_nxt);
+    if (t + 1 < ntot) SA_ISSUE_TILE(t + 1, cur ^ 1, e_nxt);
+    const int e_this = e_cur;
+    e_cur = e_nxt;
+    r_nxt = (int)tlist[min(t + 2, kMaxSeq / BK - 1)];
 
     // ---- what this wave keeps of the tile: a 64-bit mask per lane over the key slots ---------
     // slot c (0..59 used) stands for key_local = c + 4*gg; see the accumulator layout below.
@@ -382,9 +392,9 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
     uint64_t km;
     int lim = 63;
     if (t < ntr) {
-      const int kt = __builtin_amdgcn_readfirstlane((int)tlist[t]);
+      const int kt = e_this & 0xFFF;
       const int j0 = kt * BK;
-      const bool bk = (((wv < 2 ? kept0 : kept1)[kt >> 5] >> (kt & 31)) & 1u) != 0;
+      const bool bk = ((e_this >> (wv < 2 ? 14 : 15)) & 1) != 0;
       const bool beyond = j0 > min(r0 + 31, N - 1);
       active = !beyond && bk;
       const uint64_t vm = has_cols ? ((uint64_t)uload(colbm, 2 * kt) | ((uint64_t)uload(colbm, 2 * kt + 1) << 32)) : 0ull;
