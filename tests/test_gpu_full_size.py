@@ -99,3 +99,31 @@ def test_counters_match_oracle_mask_count():
     ses.prefill(Qd, Kd, Vd, O2)
     torch.cuda.synchronize()
     assert torch.equal(O, O2)
+
+
+def test_decode_step_at_cfg5_128k():
+    # the decode step at the benchmark's size and launch configuration (bench.py --decode):
+    # every head against the fp64 oracle, run-time patterns, a position behind a few generated keys
+    from oracle import decode as dec
+    print("case decode cfg5", flush=True)
+    wl = gen.WORKLOADS["cfg5"]
+    data = gen.generate(wl)
+    Hq, Hkv, N, b, d = wl.n_q_heads, wl.n_kv_heads, wl.seq_len, wl.block, wl.head_dim
+    pad = 64
+    Kx = np.concatenate([data["K"], data["K"][:, :pad]], axis=1)
+    Vx = np.concatenate([data["V"], data["V"][:, :pad]], axis=1)
+    ses = sa.Session(Hq, Hkv, N, b, wl.last_q, keep=wl.keep, kv_head_stride=(N + pad) * d)
+    Qd, Kd, Vd = dev_bf16(data["Q"]), dev_bf16(Kx), dev_bf16(Vx)
+    ses.estimate(Qd, Kd)
+    ses.build_index(None)
+    torch.cuda.synchronize()
+    ix = download_index(ses)
+    pos = N + 7
+    q = Qd[:, N - 1].contiguous()
+    o = torch.empty_like(q)
+    ses.decode(q, Kd, Vd, pos, o)
+    torch.cuda.synchronize()
+    ref, cnt = dec.decode_step(data["Q"][:, N - 1], Kx, Vx, b, ix, N, pos)
+    err = np.abs(host_f64(o) - ref)
+    assert err.max() <= 2e-2 and err.mean() <= 2e-3, (float(err.max()), float(err.mean()))
+    assert (cnt >= pos - N + 1).all()
