@@ -33,14 +33,13 @@ void carve(sa_ctx *c) {
   c->off[2] = o; o += align256((size_t)s.Hq * s.nchunks * sa::kWin * 8);
   c->off[3] = o; o += align256((size_t)s.Hq * sa::kWin * 8);
   c->off[4] = o; o += align256((size_t)s.Hq * (s.N / 32) * 4);
-  c->off[5] = o; o += align256((size_t)s.Hq * (s.N / 32) * 4);
   const size_t kvg = (size_t)s.Hq * ((s.k_v + 63) / 64 * 64) * (size_t)s.kv_rs * 2;
+  c->off[5] = o; o += align256(kvg);
   c->off[6] = o; o += align256(kvg);
-  c->off[7] = o; o += align256(kvg);
-  c->off[8] = o; o += 256;
-  c->off[9] = o; o += align256(sa::index_scratch_bytes(s.Hq));
-  c->off[10] = o; o += align256((size_t)s.Hq * (s.N / 32) * 4);
-  c->off[11] = o; o += align256(sa::decode_partial_bytes(s));
+  c->off[7] = o; o += 256;
+  c->off[8] = o; o += align256(sa::index_scratch_bytes(s.Hq));
+  c->off[9] = o; o += align256((size_t)s.Hq * (s.N / 32) * 4);
+  c->off[10] = o; o += align256(sa::decode_partial_bytes(s));
   c->ws_bytes = o;
 }
 
@@ -201,14 +200,13 @@ sa_status sa_set_workspace(sa_ctx *c, void *dev, size_t bytes) {
   c->ws.kblk = (float *)(p + c->off[1]);
   c->ws.part = (float2 *)(p + c->off[2]);
   c->ws.stats = (float2 *)(p + c->off[3]);
-  c->ws.offbits = (uint32_t *)(p + c->off[4]);
-  c->ws.colbits = (uint32_t *)(p + c->off[5]);
-  c->ws.kg = (uint16_t *)(p + c->off[6]);
-  c->ws.vg = (uint16_t *)(p + c->off[7]);
-  c->ws.queue = (unsigned int *)(p + c->off[8]);
-  c->ws.idx = (void *)(p + c->off[9]);
-  c->ws.colprefix = (int32_t *)(p + c->off[10]);
-  c->ws.dec_part = (float *)(p + c->off[11]);
+  c->ws.colbits = (uint32_t *)(p + c->off[4]);
+  c->ws.kg = (uint16_t *)(p + c->off[5]);
+  c->ws.vg = (uint16_t *)(p + c->off[6]);
+  c->ws.queue = (unsigned int *)(p + c->off[7]);
+  c->ws.idx = (void *)(p + c->off[8]);
+  c->ws.colprefix = (int32_t *)(p + c->off[9]);
+  c->ws.dec_part = (float *)(p + c->off[10]);
   c->have_ws = true;
   return SA_OK;
 }

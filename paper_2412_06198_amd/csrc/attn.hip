@@ -1,17 +1,19 @@
 // Sparse causal prefill attention for gfx950 (Alg. 2 / Alg. 3 "Compute Sparse
 // Attention": softmax over the kept keys only, then the product with V).
 //
-// One workgroup = 128 query rows of one head (4 waves x 32 rows).  The key axis
-// is walked in tiles of 64 keys:
-//   * range tiles  - aligned key tiles that hold a kept block of the CSR or a
-//                    piece of a selected diagonal;
-//   * gather tiles - 64 selected key columns, rows fetched one by one (each a
-//                    256-byte coalesced read).
+// One workgroup = 128 query rows of one head (4 waves x 32 rows), two workgroups
+// per compute unit, fed from work queues.  A (head, row block) item has two phases:
+//   * tiles of 64 keys through LDS, shared by the four waves:
+//       range tiles  - aligned key tiles of the key blocks the CSR keeps;
+//       gather tiles - 64 selected key columns, gathered once per call into
+//                      contiguous buffers, so that they are read like any tile;
+//   * selected diagonals, one 32-key tile per wave and offset, without barriers.
 // A key is counted once: selected columns are masked out of range tiles and
-// served by the gather tiles only.  Per tile each wave computes
-// S^T = K Q^T (keys x queries) with v_mfma_f32_32x32x16_bf16, so that one lane
-// owns one query: the online softmax needs a single cross-lane exchange, and
-// the probabilities are already laid out as the B operand of O^T += V^T P^T.
+// diagonal entries whose key is a selected column or lies in a kept block are
+// dropped.  Per tile each wave computes S^T = K Q^T (keys x queries) with
+// v_mfma_f32_32x32x16_bf16, so that one lane owns one query: the online softmax
+// needs a single cross-lane exchange, and the probabilities are already laid out
+// as the B operand of O^T += V^T P^T.
 #include "sa_internal.h"
 
 namespace sa {
@@ -30,7 +32,7 @@ struct AttnArgs {
   const uint16_t *Q, *K, *V;
   uint16_t *O;
   const int32_t *n_cols, *cols, *n_offs, *offs, *rowptr, *blkcols;
-  const uint32_t *offbits, *colbits;
+  const uint32_t *colbits;   // [Hq][N/32] membership bitmap of the selected columns
   const int32_t *colprefix;  // [Hq][N/32] selected columns before each word of colbits
   uint16_t *Kg, *Vg;  // [Hq][kvg_rows][kv_rs] selected key columns, gathered once per call
   int kvg_rows;
@@ -44,27 +46,19 @@ struct AttnArgs {
   unsigned long long *counters;  // instrumentation only: {32x32 sub-tiles multiplied, kept (query,key) pairs}
 };
 
-// Membership bitmaps of the selected columns and diagonal offsets, and the running count of
-// selected columns before each bitmap word, one block of 256 threads per head.
-__global__ __launch_bounds__(256) void index_bitmaps_kernel(const int32_t *n_cols, const int32_t *cols,
-                                     const int32_t *n_offs, const int32_t *offs, int k_v, int k_s,
-                                     int N, uint32_t *colbits, uint32_t *offbits,
-                                     int32_t *colprefix, unsigned int *queue) {
+// Membership bitmap of the selected columns and the running count of selected columns before
+// each bitmap word, one block of 256 threads per head; also resets the work-queue heads.
+__global__ __launch_bounds__(256) void index_bitmaps_kernel(const int32_t *n_cols, const int32_t *cols, int k_v,
+                                     int N, uint32_t *colbits, int32_t *colprefix,
+                                     unsigned int *queue) {
   const int h = blockIdx.x, nw = N / 32;
   if (h == 0 && threadIdx.x < 8) queue[threadIdx.x] = 0u;
-  for (int i = threadIdx.x; i < nw; i += blockDim.x) {
-    colbits[(size_t)h * nw + i] = 0u;
-    offbits[(size_t)h * nw + i] = 0u;
-  }
+  for (int i = threadIdx.x; i < nw; i += blockDim.x) colbits[(size_t)h * nw + i] = 0u;
   __syncthreads();
-  const int nc = min(max(n_cols[h], 0), k_v), no = min(max(n_offs[h], 0), k_s);
+  const int nc = min(max(n_cols[h], 0), k_v);
   for (int i = threadIdx.x; i < nc; i += blockDim.x) {
     const int c = cols[(size_t)h * k_v + i];
     if (c >= 0 && c < N) atomicOr(&colbits[(size_t)h * nw + (c >> 5)], 1u << (c & 31));
-  }
-  for (int i = threadIdx.x; i < no; i += blockDim.x) {
-    const int o = offs[(size_t)h * k_s + i];
-    if (o >= 0 && o < N) atomicOr(&offbits[(size_t)h * nw + (o >> 5)], 1u << (o & 31));
   }
   // exclusive prefix popcount over the column bitmap: thread t owns a contiguous run of words
   __shared__ int s_run[256];
@@ -86,18 +80,6 @@ __global__ __launch_bounds__(256) void index_bitmaps_kernel(const int32_t *n_col
     colprefix[(size_t)h * nw + w] = run;
     run += __popc(colbits[(size_t)h * nw + w]);
   }
-}
-
-__device__ inline uint32_t bits_word(const uint32_t *__restrict__ bm, int nw, int wi) {
-  return (wi >= 0 && wi < nw) ? bm[wi] : 0u;
-}
-
-// 64 bits of a bitmap starting at bit position `pos` (may be negative or run past the end).
-__device__ inline uint64_t bits_window64(const uint32_t *__restrict__ bm, int nw, int pos) {
-  const int wi = pos >> 5, sh = pos & 31;  // arithmetic shift: floor for negatives
-  const uint64_t lo = (uint64_t)bits_word(bm, nw, wi) | ((uint64_t)bits_word(bm, nw, wi + 1) << 32);
-  const uint64_t hi = (uint64_t)bits_word(bm, nw, wi + 2);
-  return sh ? ((lo >> sh) | (hi << (64 - sh))) : lo;
 }
 
 // Read-only words at a wave-uniform address: through the constant address space these become
@@ -137,7 +119,6 @@ __global__ __launch_bounds__(256) void gather_columns_kernel(AttnArgs p) {
 // LDS tiles are 64 rows x 256 B with the 16-byte chunks of a row XOR-swizzled (no padding):
 //   K: chunk c of row r sits at chunk c ^ (r & 15)      -> b128 reads of 16 rows hit 64 banks
 //   V: chunk c of row r sits at chunk c ^ ((r & 3) << 2) -> the transposing b64 reads do
-__device__ inline int kswz(int row, int chunk) { return row * 128 + ((chunk ^ (row & 15)) << 3); }
 __device__ inline int vswz(int row, int chunk) { return row * 128 + ((chunk ^ ((row & 3) << 2)) << 3); }
 
 template <bool STATS>
@@ -713,15 +694,15 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
 hipError_t launch_sparse_prefill(const Shape &sh, const Workspace &ws, const uint16_t *Q,
                                  const uint16_t *K, const uint16_t *V, sa_index idx, uint16_t *O,
                                  unsigned long long *counters, hipStream_t st) {
-  index_bitmaps_kernel<<<sh.Hq, 256, 0, st>>>(idx.n_cols, idx.cols, idx.n_offs, idx.offs, sh.k_v,
-                                              sh.k_s, sh.N, ws.colbits, ws.offbits, ws.colprefix, ws.queue);
+  index_bitmaps_kernel<<<sh.Hq, 256, 0, st>>>(idx.n_cols, idx.cols, sh.k_v, sh.N, ws.colbits, ws.colprefix,
+                                              ws.queue);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   AttnArgs a;
   a.Q = Q; a.K = K; a.V = V; a.O = O;
   a.n_cols = idx.n_cols; a.cols = idx.cols; a.n_offs = idx.n_offs; a.offs = idx.offs;
   a.rowptr = idx.rowptr; a.blkcols = idx.blkcols;
-  a.offbits = ws.offbits; a.colbits = ws.colbits; a.colprefix = ws.colprefix;
+  a.colbits = ws.colbits; a.colprefix = ws.colprefix;
   a.Hq = sh.Hq; a.Hkv = sh.Hkv; a.g = sh.g; a.N = sh.N; a.b = sh.b; a.nb = sh.nb;
   a.nT = (sh.N + BQ - 1) / BQ;
   a.k_v = sh.k_v; a.k_s = sh.k_s; a.cap_b = sh.cap_b;

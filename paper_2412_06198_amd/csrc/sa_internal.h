@@ -30,7 +30,7 @@ struct Workspace {
   float *qblk, *kblk;             // [Hq][nb][128], [Hkv][nb][128] block means
   float2 *part;                   // [Hq][nchunks][64] partial (max, sum) of the window rows
   float2 *stats;                  // [Hq][64] (max * scale*log2e, 1/sum)
-  uint32_t *offbits, *colbits;    // [Hq][N/32] membership bitmaps of offs / cols
+  uint32_t *colbits;              // [Hq][N/32] membership bitmap of the selected columns
   int32_t *colprefix;             // [Hq][N/32] number of selected columns before each word of colbits
   float *dec_part;                // [Hq][splits][132] partial (max, sum, output) of the decode step
   unsigned int *queue;            // [8] work-queue heads of the attention kernel
@@ -55,7 +55,7 @@ struct sa_ctx {
   sa::Fork fork;
   bool have_ws;
   size_t ws_bytes;
-  size_t off[12];
+  size_t off[11];
   char err[256];
 };
 
