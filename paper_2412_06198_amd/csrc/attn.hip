@@ -254,12 +254,13 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
       }
       int pos = base + incl - cnt;
       uint32_t wbits = word;
+      // the keep words are read once: the loop below then has no LDS read to wait for
+      const uint32_t k0 = (w0 + lane < nwords) ? kept0[w0 + lane] : 0u, k1 = (w0 + lane < nwords) ? kept1[w0 + lane] : 0u;
       while (wbits) {
         const int bit = __ffs(wbits) - 1;
         wbits &= wbits - 1;
         // entry: key tile (bits 0..11), kept by waves 0,1 (bit 14) / by waves 2,3 (bit 15)
-        tlist[pos++] = (uint16_t)(((w0 + lane) * 32 + bit) | (((kept0[w0 + lane] >> bit) & 1u) << 14) |
-                                  (((kept1[w0 + lane] >> bit) & 1u) << 15));
+        tlist[pos++] = (uint16_t)(((w0 + lane) * 32 + bit) | (((k0 >> bit) & 1u) << 14) | (((k1 >> bit) & 1u) << 15));
       }
       base += __shfl(incl, 63);
     }
