@@ -13,9 +13,9 @@ import paper_2412_06198_amd as sa
 pytestmark = pytest.mark.gpu
 
 
-def _whole_path(name, n_rows, margin_check=True):
+def _whole_path(name, n_rows, margin_check=True, wl=None):
     print(f"case full-size {name}", flush=True)
-    wl = gen.WORKLOADS[name]
+    wl = gen.WORKLOADS[name] if wl is None else wl
     data = gen.generate(wl)
     N, b, w, Hq = wl.seq_len, wl.block, wl.last_q, wl.n_q_heads
     ses = sa.Session(Hq, wl.n_kv_heads, N, b, w, keep=wl.keep)
@@ -78,6 +78,14 @@ def test_cfg4_64k():
 
 def test_cfg5_128k_one_layer():
     _whole_path("cfg5", 48)
+
+
+def test_longest_supported_sequence_256k():
+    # the library's limit: 262144 tokens, block 64 (4096 key tiles, the widest tile-list entries),
+    # one KV head (all eight work queues on one head), one head per pattern
+    wl = gen.scaled(gen.WORKLOADS["cfg5"], name="max256k", seq_len=262144, block=64, n_q_heads=4,
+                    n_kv_heads=1, keep=0.01, hot_block=64, seed=9000)
+    _whole_path("max256k", 40, wl=wl)
 
 
 def test_counters_match_oracle_mask_count():
