@@ -26,6 +26,18 @@ constexpr float kLog2e = 1.4426950408889634f;
 
 __device__ inline float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
 
+// Block means are kept as two bf16 numbers, head + remainder (x = hi + lo to about 2^-17 |x|), so
+// that the block map can form their products on the bf16 matrix pipe: hi.hi + hi.lo + lo.hi with
+// fp32 accumulation differs from the fp32 product by about 2^-16 of it.  Row r of a means array
+// holds 128 heads followed by 128 remainders (512 bytes, the size of the fp32 row it replaces).
+__device__ inline void store_split(float *means_row, int d, float x) {
+  const __bf16 hi = (__bf16)x;
+  const __bf16 lo = (__bf16)(x - (float)hi);
+  uint16_t *row = (uint16_t *)means_row;
+  row[d] = __builtin_bit_cast(uint16_t, hi);
+  row[kHeadDim + d] = __builtin_bit_cast(uint16_t, lo);
+}
+
 // ------------------------------------------------------------------ Q block means
 // grid (nb, Hq), 256 threads: thread = (row group of 16, 16-byte column); all RPT = b/16 loads of
 // a thread are in flight before the first sum.  The kernel is pure HBM streaming and runs beside
@@ -62,7 +74,7 @@ __global__ __launch_bounds__(256) void q_block_mean_kernel(const uint16_t *__res
     float sum = 0.f;
 #pragma unroll
     for (int r = 0; r < 16; ++r) sum += red[r][tid];
-    qblk[((size_t)h * sh.nb + R) * kHeadDim + tid] = sum * (1.0f / (float)sh.b);
+    store_split(qblk + ((size_t)h * sh.nb + R) * kHeadDim, tid, sum * (1.0f / (float)sh.b));
   }
 }
 
@@ -169,8 +181,8 @@ __global__ __launch_bounds__(256) void window_stats_kernel(const uint16_t *__res
     if (do_means) {
       if (pending >= 0 && tid < kHeadDim) {
         const float(*ps)[kHeadDim] = ksum[pending & 1];
-        kblk[((size_t)kvh * sh.nb + pending) * kHeadDim + tid] =
-            ((ps[0][tid] + ps[1][tid]) + (ps[2][tid] + ps[3][tid])) * (1.0f / (float)sh.b);
+        store_split(kblk + ((size_t)kvh * sh.nb + pending) * kHeadDim, tid,
+                    ((ps[0][tid] + ps[1][tid]) + (ps[2][tid] + ps[3][tid])) * (1.0f / (float)sh.b));
       }
       pending = -1;
 #pragma unroll
@@ -243,8 +255,8 @@ __global__ __launch_bounds__(256) void window_stats_kernel(const uint16_t *__res
     __syncthreads();
     if (pending >= 0 && tid < kHeadDim) {
       const float(*ps)[kHeadDim] = ksum[pending & 1];
-      kblk[((size_t)kvh * sh.nb + pending) * kHeadDim + tid] =
-          ((ps[0][tid] + ps[1][tid]) + (ps[2][tid] + ps[3][tid])) * (1.0f / (float)sh.b);
+      store_split(kblk + ((size_t)kvh * sh.nb + pending) * kHeadDim, tid,
+                  ((ps[0][tid] + ps[1][tid]) + (ps[2][tid] + ps[3][tid])) * (1.0f / (float)sh.b));
     }
   }
 #pragma unroll
@@ -435,13 +447,14 @@ __global__ __launch_bounds__(256) void window_scores_kernel(const uint16_t *__re
 
 // ------------------------------------------------------------------ block map
 // blk[h][R][C] = softmax over C <= R of scale * Qblk[R].Kblk[C]; entries C > R are 0.
-// One workgroup = 16 rows of one head.  v_mfma_f32_16x16x4_f32 forms 16x16 logit tiles
-// (lane l: column l%16, rows 4(l/16) + r); the column tiles of the strip go round-robin to the
-// eight waves and stay in registers (MT tiles per wave) until the row maxima and sums are known,
-// so blk is written exactly once.  The contraction index is split so that MFMA step (e, x) of
-// lane group g = l/16 takes element 16e + 4g + x of a row: one load instruction then reads 64
-// contiguous bytes of each of the 16 rows.  Eight waves (and few registers each) rather than
-// four: the operand reads come from another XCD's writes, and only occupancy hides them.
+// One workgroup = 16 rows of one head.  The means arrive split into bf16 head + remainder (see
+// store_split), and v_mfma_f32_16x16x32_bf16 forms the 16x16 logit tiles from head x head and the
+// two cross products: fp32-grade logits (a bf16 product alone would break the 1e-3 tolerance of
+// blk) at a fifth of the cycles of the fp32 matrix instruction.  Lane l of a tile: column l%16,
+// rows 4(l/16) + r.  The column tiles of the strip go round-robin to the eight waves and stay in
+// registers (MT tiles per wave) until the row maxima and sums are known, so blk is written exactly
+// once.  Eight waves (and few registers each) rather than four: the operand reads come from
+// another XCD's writes, and only occupancy hides them.
 // grid ceil(nb/16) * Hq, 512 threads; strips are taken longest first.
 constexpr int kMapWaves = 8;
 
@@ -475,44 +488,52 @@ __global__ __launch_bounds__(64 * kMapWaves, (MT <= 8 ? 4 : 2)) void block_map_k
   const float *qsrc = qblk + (size_t)h * nb * kHeadDim;
   const float *ksrc = kblk + (size_t)(h / sh.g) * nb * kHeadDim;
 
-  float4 a4[8];
+  // operands of v_mfma_f32_16x16x32_bf16: lane (n = row of A / column of B, g) holds elements
+  // 32 st + 8 g .. + 7 of its mean, st = 0..3: 16 bytes of heads and 16 bytes of remainders per step
+  bf16x8 ah[4], al[4];
   {
-    const float *ap = qsrc + (size_t)min(R0 + n, nb - 1) * kHeadDim + 4 * g;
+    const uint16_t *ap = (const uint16_t *)(qsrc + (size_t)min(R0 + n, nb - 1) * kHeadDim) + 8 * g;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) a4[e] = *(const float4 *)(ap + 16 * e);
+    for (int st = 0; st < 4; ++st) {
+      ah[st] = *(const bf16x8 *)(ap + 32 * st);
+      al[st] = *(const bf16x8 *)(ap + kHeadDim + 32 * st);
+    }
   }
   f32x4 acc[MT];
-  float4 b4[8];
+  bf16x8 bh[4], bl[4];
   if (wv < T) {
-    const float *bp = ksrc + (size_t)min(16 * wv + n, nb - 1) * kHeadDim + 4 * g;
+    const uint16_t *bp = (const uint16_t *)(ksrc + (size_t)min(16 * wv + n, nb - 1) * kHeadDim) + 8 * g;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) b4[e] = *(const float4 *)(bp + 16 * e);
+    for (int st = 0; st < 4; ++st) {
+      bh[st] = *(const bf16x8 *)(bp + 32 * st);
+      bl[st] = *(const bf16x8 *)(bp + kHeadDim + 32 * st);
+    }
   }
 #pragma unroll
   for (int k = 0; k < MT; ++k) {
     const int tc = kMapWaves * k + wv;
     if (tc < T) {
-      float4 bn[8];
-      if (tc + kMapWaves < T) {
-        const float *bp = ksrc + (size_t)min(16 * (tc + kMapWaves) + n, nb - 1) * kHeadDim + 4 * g;
+      {
+        const uint16_t *bp = (const uint16_t *)(ksrc + (size_t)min(16 * tc + n, nb - 1) * kHeadDim) + 8 * g;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) bn[e] = *(const float4 *)(bp + 16 * e);
+        for (int st = 0; st < 4; ++st) {
+          bh[st] = *(const bf16x8 *)(bp + 32 * st);
+          bl[st] = *(const bf16x8 *)(bp + kHeadDim + 32 * st);
+        }
       }
-      f32x4 d = {0.f, 0.f, 0.f, 0.f};
+      // three independent chains: heads x heads, and the two cross terms (remainder x remainder,
+      // about 2^-18 of the product, is dropped)
+      f32x4 dhh = {0.f, 0.f, 0.f, 0.f}, dhl = dhh, dlh = dhh;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        d = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[e].x, b4[e].x, d, 0, 0, 0);
-        d = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[e].y, b4[e].y, d, 0, 0, 0);
-        d = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[e].z, b4[e].z, d, 0, 0, 0);
-        d = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[e].w, b4[e].w, d, 0, 0, 0);
+      for (int st = 0; st < 4; ++st) {
+        dhh = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah[st], bh[st], dhh, 0, 0, 0);
+        dhl = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah[st], bl[st], dhl, 0, 0, 0);
+        dlh = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al[st], bh[st], dlh, 0, 0, 0);
       }
+      const f32x4 d = dhh + (dhl + dlh);
       const int C = 16 * tc + n;
 #pragma unroll
       for (int r = 0; r < 4; ++r) acc[k][r] = (C <= R0 + 4 * g + r) ? d[r] * c2 : -INFINITY;
-      if (tc + kMapWaves < T) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) b4[e] = bn[e];
-      }
     } else {
 #pragma unroll
       for (int r = 0; r < 4; ++r) acc[k][r] = -INFINITY;
