@@ -39,48 +39,12 @@ struct AttnArgs {
   int Hq, Hkv, g, N, b, nb, nT, k_v, k_s, cap_b;
   int64_t q_hs, q_rs, kv_hs, kv_rs;
   float c;  // softmax scale * log2(e)
-  unsigned int *queue;           // [8] work-queue heads, zeroed by index_bitmaps_kernel
+  unsigned int *queue;           // [8] work-queue heads, zeroed by index_prepare_kernel
   int n_items;  // (head, row block) items in all
   int xs;       // queues (XCDs) that share one KV head at a time: 1, 2, 4 or 8
   int qcap;     // tickets per queue, holes of the id space included
   unsigned long long *counters;  // instrumentation only: {32x32 sub-tiles multiplied, kept (query,key) pairs}
 };
-
-// Membership bitmap of the selected columns and the running count of selected columns before
-// each bitmap word, one block of 256 threads per head; also resets the work-queue heads.
-__global__ __launch_bounds__(256) void index_bitmaps_kernel(const int32_t *n_cols, const int32_t *cols, int k_v,
-                                     int N, uint32_t *colbits, int32_t *colprefix,
-                                     unsigned int *queue) {
-  const int h = blockIdx.x, nw = N / 32;
-  if (h == 0 && threadIdx.x < 8) queue[threadIdx.x] = 0u;
-  for (int i = threadIdx.x; i < nw; i += blockDim.x) colbits[(size_t)h * nw + i] = 0u;
-  __syncthreads();
-  const int nc = min(max(n_cols[h], 0), k_v);
-  for (int i = threadIdx.x; i < nc; i += blockDim.x) {
-    const int c = cols[(size_t)h * k_v + i];
-    if (c >= 0 && c < N) atomicOr(&colbits[(size_t)h * nw + (c >> 5)], 1u << (c & 31));
-  }
-  // exclusive prefix popcount over the column bitmap: thread t owns a contiguous run of words
-  __shared__ int s_run[256];
-  __syncthreads();
-  const int tid = threadIdx.x, per = (nw + 255) / 256;
-  const int w0 = min(tid * per, nw), w1 = min(w0 + per, nw);
-  int mine = 0;
-  for (int w = w0; w < w1; ++w) mine += __popc(colbits[(size_t)h * nw + w]);
-  s_run[tid] = mine;
-  __syncthreads();
-  for (int d = 1; d < 256; d <<= 1) {
-    const int add = tid >= d ? s_run[tid - d] : 0;
-    __syncthreads();
-    s_run[tid] += add;
-    __syncthreads();
-  }
-  int run = s_run[tid] - mine;
-  for (int w = w0; w < w1; ++w) {
-    colprefix[(size_t)h * nw + w] = run;
-    run += __popc(colbits[(size_t)h * nw + w]);
-  }
-}
 
 // Read-only words at a wave-uniform address: through the constant address space these become
 // scalar loads, which neither occupy the vector memory path nor count in vmcnt.
@@ -96,10 +60,53 @@ __device__ inline uint32_t bits_window32(const uint32_t *bm, int nw, int pos) {
   return (uint32_t)(((uint64_t)lo | ((uint64_t)hi << 32)) >> sh);
 }
 
-// The selected key columns of every head, copied once into contiguous [k][d] buffers so that
-// the attention kernel reads gather tiles like any other tile.  grid (ceil(k_v/64), Hq).
-__global__ __launch_bounds__(256) void gather_columns_kernel(AttnArgs p) {
-  const int h = blockIdx.y, g = blockIdx.x, tid = threadIdx.x;
+// What the attention kernel needs from the index before it starts, in one launch of 256-thread
+// blocks.  Blocks 0 .. Hq-1: membership bitmap of a head's selected columns and the running count
+// of selected columns before each bitmap word (built in LDS, written out once); block 0 also
+// resets the work-queue heads.  The other blocks, (gather tile g, head h) = Hq + h * ntile + g:
+// the selected key columns of every head are copied once into contiguous [k][d] buffers so that
+// the attention kernel reads gather tiles like any other tile.
+__global__ __launch_bounds__(256) void index_prepare_kernel(AttnArgs p, unsigned int *queue) {
+  __shared__ uint32_t bm[kMaxSeq / 32];
+  __shared__ int wsum[4];
+  const int tid = threadIdx.x;
+  if ((int)blockIdx.x < p.Hq) {
+    const int h = blockIdx.x, nw = p.N / 32, lane = tid & 63, wv = tid >> 6;
+    if (h == 0 && tid < 8) queue[tid] = 0u;
+    for (int i = tid; i < nw; i += 256) bm[i] = 0u;
+    __syncthreads();
+    const int nc = min(max(p.n_cols[h], 0), p.k_v);
+    for (int i = tid; i < nc; i += 256) {
+      const int c = p.cols[(size_t)h * p.k_v + i];
+      if (c >= 0 && c < p.N) atomicOr(&bm[c >> 5], 1u << (c & 31));
+    }
+    __syncthreads();
+    // exclusive prefix popcount: thread t owns a contiguous run of words
+    const int per = (nw + 255) / 256;
+    const int w0 = min(tid * per, nw), w1 = min(w0 + per, nw);
+    int mine = 0;
+    for (int w = w0; w < w1; ++w) mine += __popc(bm[w]);
+    int incl = mine;
+    for (int dd = 1; dd < 64; dd <<= 1) {
+      const int o = __shfl_up(incl, dd);
+      if (lane >= dd) incl += o;
+    }
+    if (lane == 63) wsum[wv] = incl;
+    __syncthreads();
+    int run = incl - mine;
+    for (int k = 0; k < wv; ++k) run += wsum[k];
+    uint32_t *cb = const_cast<uint32_t *>(p.colbits) + (size_t)h * nw;
+    int32_t *cp = const_cast<int32_t *>(p.colprefix) + (size_t)h * nw;
+    for (int w = w0; w < w1; ++w) {
+      const uint32_t word = bm[w];
+      cb[w] = word;
+      cp[w] = run;
+      run += __popc(word);
+    }
+    return;
+  }
+  const int ntile = p.kvg_rows / BK;
+  const int h = ((int)blockIdx.x - p.Hq) / ntile, g = ((int)blockIdx.x - p.Hq) % ntile;
   const int nc = min(max(p.n_cols[h], 0), p.k_v);
   if (g * BK >= nc) return;
   const int kvh = h / p.g;
@@ -695,11 +702,7 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
 hipError_t launch_sparse_prefill(const Shape &sh, const Workspace &ws, const uint16_t *Q,
                                  const uint16_t *K, const uint16_t *V, sa_index idx, uint16_t *O,
                                  unsigned long long *counters, hipStream_t st) {
-  index_bitmaps_kernel<<<sh.Hq, 256, 0, st>>>(idx.n_cols, idx.cols, sh.k_v, sh.N, ws.colbits, ws.colprefix,
-                                              ws.queue);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  AttnArgs a;
+  AttnArgs a = {};
   a.Q = Q; a.K = K; a.V = V; a.O = O;
   a.n_cols = idx.n_cols; a.cols = idx.cols; a.n_offs = idx.n_offs; a.offs = idx.offs;
   a.rowptr = idx.rowptr; a.blkcols = idx.blkcols;
@@ -711,7 +714,9 @@ hipError_t launch_sparse_prefill(const Shape &sh, const Workspace &ws, const uin
   a.c = sh.scale * 1.4426950408889634f;
   a.counters = counters;
   a.Kg = ws.kg; a.Vg = ws.vg; a.kvg_rows = (sh.k_v + BK - 1) / BK * BK;
-  gather_columns_kernel<<<dim3(a.kvg_rows / BK, sh.Hq), 256, 0, st>>>(a);
+  index_prepare_kernel<<<sh.Hq + a.kvg_rows / BK * sh.Hq, 256, 0, st>>>(a, ws.queue);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
   a.queue = ws.queue;
   a.n_items = a.nT * sh.Hq;
   // KV heads in progress together: as many as there are queues, unless their K and V rows
