@@ -52,7 +52,7 @@ def cpu_baseline(orc, data, wl, bud, sample_rows):
     }
 
 
-def run_workload(name, steps, warmup, layers, with_cpu, sample_rows, with_dense=False):
+def run_workload(name, steps, warmup, layers, with_cpu, sample_rows, with_dense=False, block_select=0):
     import numpy as np
     import torch
 
@@ -62,7 +62,7 @@ def run_workload(name, steps, warmup, layers, with_cpu, sample_rows, with_dense=
     wl = gen.WORKLOADS[name]
     N, b, w, Hq, Hkv, d = wl.seq_len, wl.block, wl.last_q, wl.n_q_heads, wl.n_kv_heads, wl.head_dim
     dev = torch.device("cuda:0")
-    ses = sa.Session(Hq, Hkv, N, b, w, keep=wl.keep)
+    ses = sa.Session(Hq, Hkv, N, b, w, keep=wl.keep, block_select=block_select)
 
     def up(bits):
         return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(dev)
@@ -154,12 +154,70 @@ def run_workload(name, steps, warmup, layers, with_cpu, sample_rows, with_dense=
     if with_cpu:
         from oracle import oracle as orc
         bud = orc.default_budgets(N, b, wl.keep)
+        bud.block_select = block_select
         res["cpu_baseline"] = cpu_baseline(orc, first, wl, bud, sample_rows)
         log(f"[{name}] cpu_baseline {res['cpu_baseline']}")
     ses.close()
     del resident, O
     torch.cuda.empty_cache()
     return res
+
+
+def run_block_rules(name, steps):
+    """The two readings of Alg. 3's TopKBlocks side by side on one layer: one top-k over the whole
+    block map against the same fraction of every row.  Error = Frobenius distance of the sparse
+    output to the all-keys output of the same kernel, over the Block-Cluster heads."""
+    import numpy as np
+    import torch
+
+    import paper_2412_06198_amd as sa
+    from harness import gen
+
+    wl = gen.WORKLOADS[name]
+    N, b, w, Hq, Hkv, d = wl.seq_len, wl.block, wl.last_q, wl.n_q_heads, wl.n_kv_heads, wl.head_dim
+    nb = N // b
+    dev = torch.device("cuda:0")
+    data = gen.generate(wl)
+
+    def up(bits):
+        return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(dev)
+
+    Q, K, V = up(data["Q"]), up(data["K"]), up(data["V"])
+    outs, res = {}, {"workload": name}
+    for label, kw in (("all_keys", dict(local_blocks=nb, k_blocks=nb * (nb + 1) // 2)),
+                      ("global", dict(block_select=0)), ("per_row", dict(block_select=1))):
+        ses = sa.Session(Hq, Hkv, N, b, w, keep=wl.keep, **kw)
+        O = torch.empty_like(Q)
+        ov = [sa.SA_TRIANGULAR] * Hq if label == "all_keys" else None
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        tot = np.zeros(3)
+        for i in range(steps + 1):
+            ev[0].record(); ses.estimate(Q, K)
+            ev[1].record(); ses.build_index(ov)
+            ev[2].record(); ses.prefill(Q, K, V, O)
+            ev[3].record()
+            torch.cuda.synchronize()
+            if i:
+                tot += [ev[k].elapsed_time(ev[k + 1]) for k in range(3)]
+        tiles, kept = ses.prefill_counted(Q, K, V, O)
+        torch.cuda.synchronize()
+        outs[label] = (O, ses.pattern.cpu().numpy().copy(), ses.rowptr[:, nb].cpu().numpy().copy())
+        res[label] = {"phases_ms": dict(zip(("estimate", "index", "attention"), (tot / steps).round(4).tolist())),
+                      "kept_pairs": int(kept), "tiles": int(tiles)}
+        ses.close()
+    pat = outs["global"][1]
+    assert (pat == outs["per_row"][1]).all()
+    bc = np.nonzero(pat == sa.SA_BLOCK_CLUSTER)[0]
+    ref = outs["all_keys"][0].float()
+    for label in ("global", "per_row"):
+        diff = (outs[label][0].float() - ref)[torch.from_numpy(bc).to(dev)]
+        err = torch.linalg.vector_norm(diff.double(), dim=(1, 2)).cpu().numpy()
+        res[label]["block_cluster_heads"] = bc.tolist()
+        res[label]["blocks_per_bc_head"] = outs[label][2][bc].tolist()
+        res[label]["frobenius_error_per_bc_head"] = err.round(3).tolist()
+        res[label]["frobenius_error_mean"] = float(err.mean())
+        log(f"[{name}] {label}: {res[label]['phases_ms']} mean error over {len(bc)} Block-Cluster heads {err.mean():.3f}")
+    print(json.dumps({"block_rules": res}))
 
 
 def run_sweep(steps):
@@ -346,6 +404,11 @@ def main():
                     help="dense-vs-sparse time per layer from 4K to 128K tokens instead of the benchmark line")
     ap.add_argument("--search", type=int, default=0, metavar="N",
                     help="time the offline pattern search (Alg. 1) on one GQA group of N tokens instead")
+    ap.add_argument("--block-select", choices=("global", "row"), default="global",
+                    help="how Block-Cluster heads spend k_blocks: one top-k (Alg. 3 read literally) or the same "
+                         "fraction of every row block")
+    ap.add_argument("--block-rules", action="store_true",
+                    help="compare the two block rules (time, kept pairs, error against all-keys attention) instead")
     ap.add_argument("--decode", action="store_true",
                     help="time one decode step over the prefill index of --workload instead")
     a = ap.parse_args()
@@ -374,14 +437,19 @@ def main():
     if a.decode:
         run_decode(a.workload, max(a.steps, 50))
         return
+    if a.block_rules:
+        run_block_rules(a.workload, a.steps)
+        return
     if a.search:
         run_search(a.search, not a.no_cpu_baseline)
         return
-    main_res = run_workload(a.workload, a.steps, a.warmup, a.layers, not a.no_cpu_baseline, a.sample_rows)
+    bsel = 1 if a.block_select == "row" else 0
+    main_res = run_workload(a.workload, a.steps, a.warmup, a.layers, not a.no_cpu_baseline, a.sample_rows,
+                            block_select=bsel)
     also = None
     if a.also and a.also != a.workload:
         also = run_workload(a.also, max(a.steps, 20), a.warmup, min(a.layers, 2), False, a.sample_rows,
-                            with_dense=True)
+                            with_dense=True, block_select=bsel)
 
     traffic = None
     tp = os.path.join(ROOT, "profiles", f"traffic_{a.workload}.json")
@@ -398,7 +466,8 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{a.workload}: Hq={wl.n_q_heads} Hkv={wl.n_kv_heads} d={wl.head_dim} "
                                f"N={wl.seq_len} block={wl.block} last_q={wl.last_q} keep={wl.keep} "
-                               f"layers={a.layers} (seeds {wl.seed}..{wl.seed + a.layers - 1}), patterns chosen at run time"},
+                               f"layers={a.layers} (seeds {wl.seed}..{wl.seed + a.layers - 1}), patterns chosen at run time"
+                               + (", blocks chosen per row" if bsel else "")},
         "roofline": {"bound": "mfma", "kernel": "sparse_prefill_kernel",
                      "achieved": round(main_res["tflops"]["kept"], 2), "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(main_res["tflops"]["kept"] / PEAK_BF16_TFLOPS, 4),

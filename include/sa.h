@@ -61,6 +61,14 @@ typedef enum {
   SA_BLOCK_CLUSTER = 2   /* top blocks of the block-mean map (Alg. 3) */
 } sa_pattern;
 
+/* How a Block-Cluster head spends k_blocks (Alg. 3 TopKBlocks names one k_b and
+ * does not say whether it is per sequence or per query block):
+ *   SA_BLOCKS_GLOBAL   one top-k over all causal blocks of the head (the literal reading);
+ *   SA_BLOCKS_PER_ROW  row block R keeps min(R+1, ceil(k_blocks (R+1) / (nb (nb+1)/2))) blocks:
+ *                      its diagonal block and its best lower blocks, ties to the lower block id,
+ *                      i.e. the same fraction of every row (at most nb blocks above k_blocks). */
+typedef enum { SA_BLOCKS_GLOBAL = 0, SA_BLOCKS_PER_ROW = 1 } sa_block_select;
+
 typedef struct {
   int32_t n_q_heads, n_kv_heads, head_dim; /* n_q_heads % n_kv_heads == 0, <= 128 heads; head_dim must be 128 */
   int32_t seq_len, block, last_q;          /* seq_len % block == 0; block in {64,128}; 1 <= last_q <= 64 */
@@ -70,6 +78,7 @@ typedef struct {
   int32_t probe_v, probe_s, lift_num, lift_den; /* pattern rule; 0 => defaults 4,4,4,1 */
   int64_t q_head_stride, q_row_stride;     /* in elements; 0 => contiguous [H][N][d]; O uses Q's strides */
   int64_t kv_head_stride, kv_row_stride;   /* K and V; row strides must be multiples of 8 elements */
+  int32_t block_select;                    /* sa_block_select; 0 => SA_BLOCKS_GLOBAL */
 } sa_config;
 
 /* Device score buffers written by sa_estimate_patterns (Alg. 2 SumRows /

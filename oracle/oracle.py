@@ -51,6 +51,7 @@ class Budgets:
     probe_s: int = 4
     lift_num: int = 4
     lift_den: int = 1
+    block_select: int = 0   # 0: one global top-k over the block map, 1: the same fraction of every row
 
 
 @dataclass
@@ -144,7 +145,9 @@ def default_budgets(N, b, rho) -> Budgets:
 
 
 def block_capacity(N, b, bud: Budgets):
-    return max(bud.k_blocks, triangular_count(N // b, bud.sink_blocks, bud.local_blocks))
+    # the per-row rule rounds every row's share up: at most one block per row above k_blocks
+    kb = bud.k_blocks + (N // b if bud.block_select == 1 else 0)
+    return max(kb, triangular_count(N // b, bud.sink_blocks, bud.local_blocks))
 
 
 def build_index(v, s, blk, N, b, w, bud: Budgets, override=None) -> Index:
@@ -167,7 +170,7 @@ def build_index(v, s, blk, N, b, w, bud: Budgets, override=None) -> Index:
                                   bud.lift_num, bud.lift_den, _p(override, i32), cap,
                                   _p(idx.pattern, i32), _p(idx.n_cols, i32), _p(idx.cols, i32),
                                   _p(idx.n_offs, i32), _p(idx.offs, i32), _p(idx.rowptr, i32),
-                                  _p(idx.blkcols, i32))
+                                  _p(idx.blkcols, i32), bud.block_select)
     assert rc == 0
     return idx
 

@@ -363,15 +363,20 @@ static int choose_pattern(const float *v, const float *s, int N, int b, int w, i
  *   rowptr[Hq][nb+1]; blkcols[Hq][cap_b] ascending within a row, -1 padded.
  * Every head keeps the diagonal blocks (R,R).  Triangular: C < sink_blocks or
  * R-C < local_blocks.  Interval-Slash: top-k_vertical columns of v, top-k_slash
- * offsets of s.  Block-Cluster: the k_blocks-nb largest blk[R][C], C<R, one
- * global top-k over the flattened causal off-diagonal entries. */
+ * offsets of s.  Block-Cluster, block_select 0 (Alg. 3 TopKBlocks read
+ * literally): the k_blocks-nb largest blk[R][C], C<R, one global top-k over the
+ * flattened causal off-diagonal entries.  block_select 1 (the per-row reading of
+ * the same step): row R keeps keep(R) = min(R+1, ceil(k_blocks (R+1) / (nb (nb+1)/2)))
+ * blocks: its diagonal block and the keep(R)-1 largest blk[R][C], C<R (ties to
+ * the lower C), i.e. every row block gets the same fraction of its causal blocks. */
 int oracle_build_index(const float *v, const float *s, const float *blk, int Hq, int N, int b,
                        int w, int sink_blocks, int local_blocks, int k_vertical, int k_slash,
                        int k_blocks, int probe_v, int probe_s, int lift_num, int lift_den,
                        const int32_t *override, int cap_b, int32_t *pattern, int32_t *n_cols,
                        int32_t *cols, int32_t *n_offs, int32_t *offs, int32_t *rowptr,
-                       int32_t *blkcols) {
+                       int32_t *blkcols, int block_select) {
   if (N % b) return 1;
+  if (block_select != 0 && block_select != 1) return 1;
   const int nb = N / b;
   int err = 0;
 #pragma omp parallel for schedule(dynamic, 1)
@@ -401,6 +406,16 @@ int oracle_build_index(const float *v, const float *s, const float *blk, int Hq,
       for (int R = 0; R < nb; ++R)
         for (int C = 0; C <= R; ++C)
           if (C < sink_blocks || R - C < local_blocks) keep[(size_t)R * nb + C] = 1;
+    } else if (pat == PAT_BLOCK_CLUSTER && block_select == 1) {
+      const int64_t all = (int64_t)nb * (nb + 1) / 2;
+      int32_t *sel = (int32_t *)malloc(sizeof(int32_t) * (size_t)nb);
+      for (int R = 1; R < nb; ++R) {
+        int64_t keep_r = ((int64_t)k_blocks * (R + 1) + all - 1) / all;
+        if (keep_r > R + 1) keep_r = R + 1;
+        const int k = topk_full_sort(bh + (size_t)R * nb, NULL, R, (int)keep_r - 1, sel, 0, NULL);
+        for (int u = 0; u < k; ++u) keep[(size_t)R * nb + sel[u]] = 1;
+      }
+      free(sel);
     } else if (pat == PAT_BLOCK_CLUSTER) {
       const int ncand = nb * (nb - 1) / 2;
       float *sc = (float *)malloc(sizeof(float) * (size_t)(ncand > 0 ? ncand : 1));

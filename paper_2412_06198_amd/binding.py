@@ -32,7 +32,8 @@ class SaConfig(C.Structure):
                 ("probe_v", C.c_int32), ("probe_s", C.c_int32), ("lift_num", C.c_int32),
                 ("lift_den", C.c_int32),
                 ("q_head_stride", C.c_int64), ("q_row_stride", C.c_int64),
-                ("kv_head_stride", C.c_int64), ("kv_row_stride", C.c_int64)]
+                ("kv_head_stride", C.c_int64), ("kv_row_stride", C.c_int64),
+                ("block_select", C.c_int32)]
 
 
 class SaScores(C.Structure):

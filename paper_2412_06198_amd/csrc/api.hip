@@ -91,6 +91,7 @@ sa_status sa_create(const sa_config *cfg, sa_ctx **out) {
   if (cfg->k_vertical < 1 || cfg->k_slash < 1 || cfg->k_blocks < nb) return SA_ERR_INVALID_ARG;
   if (cfg->probe_v < 0 || cfg->probe_s < 0 || cfg->lift_num < 0 || cfg->lift_den < 0) return SA_ERR_INVALID_ARG;
   if (cfg->softmax_scale < 0.f) return SA_ERR_INVALID_ARG;
+  if (cfg->block_select != SA_BLOCKS_GLOBAL && cfg->block_select != SA_BLOCKS_PER_ROW) return SA_ERR_INVALID_ARG;
 
   sa_ctx *c = new (std::nothrow) sa_ctx();
   if (!c) return SA_ERR_INVALID_ARG;
@@ -105,7 +106,10 @@ sa_status sa_create(const sa_config *cfg, sa_ctx **out) {
   s.lift_num = cfg->lift_num ? cfg->lift_num : 4;
   s.lift_den = cfg->lift_den ? cfg->lift_den : 1;
   const long long tri = triangular_count(nb, s.sink, s.local);
-  const long long cap = tri > s.k_b ? tri : s.k_b;
+  s.row_select = cfg->block_select == SA_BLOCKS_PER_ROW;
+  // the per-row rule rounds every row's share up: at most one block per row above k_b
+  const long long kcap = (long long)s.k_b + (s.row_select ? nb : 0);
+  const long long cap = tri > kcap ? tri : kcap;
   if (cap > 0x7FFFFFFFll) { delete c; return SA_ERR_UNSUPPORTED; }
   s.cap_b = (int)cap;
   s.nchunks = (s.N + sa::kChunk - 1) / sa::kChunk;

@@ -16,6 +16,11 @@
 // synchronisation between workgroups, no fences or spin waits.  Two more
 // launches count and then emit the selected entries in index order (wave
 // ballots), so the result is sorted without any sort.
+//
+// With the per-row block rule (every row block of a Block-Cluster head keeps the
+// same fraction of its causal blocks) the fifth selection is switched off and
+// one more launch selects inside each row instead: one wave per row, keys in
+// registers, the threshold found bit by bit.
 #include <cstddef>
 
 #include "sa_internal.h"
@@ -64,6 +69,14 @@ __device__ inline unsigned long long fx30(unsigned bits) {
   const int sh = e - 120;   // (e - 127) - 23 + 30
   if (sh >= 0) return sh < 40 ? (m << sh) : ~0ull;
   return (-sh) < 64 ? (m >> (-sh)) : 0ull;
+}
+
+// Blocks that row block R keeps under the per-row rule: the same fraction k_b / (nb (nb+1) / 2) of
+// its R + 1 causal blocks, rounded up (the diagonal block is one of them).
+__device__ inline int row_share(const Shape &sh, int R) {
+  const long long all = (long long)sh.nb * (sh.nb + 1) / 2;
+  const long long k = ((long long)sh.k_b * (R + 1) + all - 1) / all;
+  return (int)(k < R + 1 ? k : R + 1);
 }
 
 // ---- candidate walks ---------------------------------------------------------------------------
@@ -375,7 +388,7 @@ __global__ __launch_bounds__(BT) void idx_count_kernel(IdxArgs a) {
     }
     if (lane == 0) { G->wgt[arr][gw] = gt; G->weq[arr][gw] = eq; red64[arr][wv] = ts; }
   }
-  {
+  if (!sh.row_select) {
     unsigned gt = 0, eq = 0;
     wave_rows_visit4(
         bb, nb, gw, a.PW, (nb & 3) == 0, [&](int) { gt = 0; eq = 0; },
@@ -460,6 +473,7 @@ __global__ __launch_bounds__(BT) void idx_scan_kernel(IdxArgs a) {
   }
   __syncthreads();
   const int pat = s_pat;
+  const bool bc_global = pat == SA_BLOCK_CLUSTER && !sh.row_select;
   // ---- row prefixes: thread t owns RP consecutive rows (nb <= kMaxNb) ------------------------------
   constexpr int RP = kMaxNb / BT;
   __syncthreads();
@@ -469,9 +483,11 @@ __global__ __launch_bounds__(BT) void idx_scan_kernel(IdxArgs a) {
     const int R = RP * tid + j;
     unsigned g = 0, e = 0;
     if (R < nb) {
-      if (pat == SA_BLOCK_CLUSTER) {
+      if (bc_global) {
         g = G->rowgt[R];
         e = G->roweq[R];
+      } else if (pat == SA_BLOCK_CLUSTER) {
+        g = (unsigned)row_share(sh, R);
       } else if (pat == SA_TRIANGULAR) {
         const int bs = max(R - sh.local + 1, 0);  // row R keeps C < min(sink, band start) and the band
         g = (unsigned)(min(sh.sink, bs) + (R - bs + 1));
@@ -492,7 +508,7 @@ __global__ __launch_bounds__(BT) void idx_scan_kernel(IdxArgs a) {
   for (int j = 0; j < RP; ++j) {
     const int R = RP * tid + j;
     if (R < nb) {
-      if (pat == SA_BLOCK_CLUSTER) {
+      if (bc_global) {
         G->rowgt[R] = eg;
         G->roweq[R] = ee;
         rp[R] = (int)(eg + min(ee, need[4]) + (unsigned)R);  // R forced diagonals above this row
@@ -502,11 +518,54 @@ __global__ __launch_bounds__(BT) void idx_scan_kernel(IdxArgs a) {
     }
     eg += g16[j];
     ee += e16[j];
-    if (R == nb - 1) rp[nb] = pat == SA_BLOCK_CLUSTER ? a.ksel[4] + nb : (int)eg;
+    if (R == nb - 1) rp[nb] = bc_global ? a.ksel[4] + nb : (int)eg;
   }
 }
 
 // ---- emission ------------------------------------------------------------------------------------------
+// Per-row block rule, one wave per row: out[0..kr) = the kr candidates C < R with the largest keys
+// (ties to the lower C) in ascending order, out[kr] = R (the forced diagonal block).  Lane l holds
+// the keys of the candidates l, l + 64, ... in registers (T of them, R <= 64 T); slots past the
+// row hold key 0, which no counting step below can reach.
+template <int T>
+__device__ inline void emit_row_select(const unsigned *row, int R, int kr, int32_t *out) {
+  const int lane = threadIdx.x & 63;
+  if (kr > 0) {
+    unsigned key[T];
+#pragma unroll
+    for (int t = 0; t < T; ++t) key[t] = (64 * t + lane < R) ? row[64 * t + lane] : 0u;
+    auto count_ge = [&](unsigned c) {  // c >= 1
+      unsigned n = 0;
+#pragma unroll
+      for (int t = 0; t < T; ++t)
+        if (64 * t < R) n += __popcll(__ballot(key[t] >= c));
+      return n;
+    };
+    // the kr-th largest key: the largest t with at least kr keys >= t, found bit by bit
+    unsigned thr = 0u;
+    for (int bit = 31; bit >= 0; --bit) {
+      const unsigned c = thr | (1u << bit);
+      if (count_ge(c) >= (unsigned)kr) thr = c;
+    }
+    const unsigned gt = thr == 0xFFFFFFFFu ? 0u : count_ge(thr + 1u);
+    const unsigned need = (unsigned)kr - gt;  // ties at the threshold, taken in index order
+    const unsigned long long below = (1ull << lane) - 1ull;
+    unsigned grun = 0, erun = 0;
+#pragma unroll
+    for (int t = 0; t < T; ++t)
+      if (64 * t < R) {
+        const bool ok = 64 * t + lane < R;
+        const bool isgt = ok && key[t] > thr, iseq = ok && key[t] == thr;
+        const unsigned long long bg = __ballot(isgt), be = __ballot(iseq);
+        const unsigned gb = grun + __popcll(bg & below), eb = erun + __popcll(be & below);
+        if (isgt || (iseq && eb < need)) out[gb + min(eb, need)] = 64 * t + lane;
+        grun += __popcll(bg);
+        erun += __popcll(be);
+      }
+  }
+  if (lane == 0) out[kr] = R;
+}
+
 __global__ __launch_bounds__(BT) void idx_emit_kernel(IdxArgs a) {
   const Shape &sh = a.sh;
   const int p = blockIdx.x, h = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -537,7 +596,9 @@ __global__ __launch_bounds__(BT) void idx_emit_kernel(IdxArgs a) {
   if (gtid == 0) { a.out.n_cols[h] = kv; a.out.n_offs[h] = ks; }
   // block CSR
   int total;
-  if (pat == SA_BLOCK_CLUSTER) {
+  if (pat == SA_BLOCK_CLUSTER && sh.row_select) {
+    total = rp[nb];  // the rows themselves are written by idx_emit_rows_kernel
+  } else if (pat == SA_BLOCK_CLUSTER) {
     const unsigned thr = G->thr[4], need = G->need[4];
     unsigned grun = 0, erun = 0;
     wave_rows_visit4(
@@ -568,6 +629,21 @@ __global__ __launch_bounds__(BT) void idx_emit_kernel(IdxArgs a) {
   for (int i = total + gtid; i < sh.cap_b; i += gthreads) bc[i] = -1;
 }
 
+// Per-row block rule: the rows of the Block-Cluster heads, wave gw of a head taking the rows
+// gw, gw + PW, ...  T = 64-key slices a row can have (nb <= 64 T).
+template <int T>
+__global__ __launch_bounds__(BT) void idx_emit_rows_kernel(IdxArgs a) {
+  const Shape &sh = a.sh;
+  const int h = blockIdx.y, nb = sh.nb;
+  if ((a.scratch + h)->pattern != SA_BLOCK_CLUSTER) return;
+  const int gw = blockIdx.x * WPB + (threadIdx.x >> 6);
+  const unsigned *hb = a.blk + (size_t)h * nb * nb;
+  const int32_t *rp = a.out.rowptr + (size_t)h * (nb + 1);
+  int32_t *bc = a.out.blkcols + (size_t)h * sh.cap_b;
+  for (int R = gw; R < nb; R += a.PW)
+    emit_row_select<T>(hb + (size_t)R * nb, R, row_share(sh, R) - 1, bc + rp[R]);
+}
+
 }  // namespace
 
 size_t index_scratch_bytes(int n_heads) { return sizeof(IdxScratch) * (size_t)n_heads; }
@@ -591,7 +667,7 @@ hipError_t launch_build_index(const Shape &sh, const Workspace &ws, sa_scores in
   a.ksel[1] = sh.probe_s < sh.N ? sh.probe_s : sh.N;
   a.ksel[2] = sh.k_v < sh.N ? sh.k_v : sh.N;
   a.ksel[3] = sh.k_s < sh.N ? sh.k_s : sh.N;
-  a.ksel[4] = (int)kb;
+  a.ksel[4] = sh.row_select ? 0 : (int)kb;   // per-row rule: selected row by row while emitting
   const dim3 grid(P, sh.Hq);
   idx_zero_kernel<<<sh.Hq, 256, 0, st>>>(a.scratch);
   idx_hist_kernel<1><<<grid, BT, 0, st>>>(a);
@@ -603,6 +679,11 @@ hipError_t launch_build_index(const Shape &sh, const Workspace &ws, sa_scores in
   idx_count_kernel<<<grid, BT, 0, st>>>(a);
   idx_scan_kernel<<<sh.Hq, BT, 0, st>>>(a);
   idx_emit_kernel<<<grid, BT, 0, st>>>(a);
+  if (sh.row_select) {
+    if (sh.nb <= 256) idx_emit_rows_kernel<4><<<grid, BT, 0, st>>>(a);
+    else if (sh.nb <= 1024) idx_emit_rows_kernel<16><<<grid, BT, 0, st>>>(a);
+    else idx_emit_rows_kernel<kMaxNb / 64><<<grid, BT, 0, st>>>(a);
+  }
   return hipGetLastError();
 }
 

@@ -92,6 +92,61 @@ def test_block_topk_ties_and_csr_invariants(vals, kb):
     assert (ix.blkcols[0, rp[nb]:] == -1).all()
 
 
+def _row_share(kb, nb, R):
+    """Blocks kept in row R by the per-row rule, written with exact fractions."""
+    from fractions import Fraction
+    import math
+    return min(R + 1, math.ceil(Fraction(kb * (R + 1), nb * (nb + 1) // 2)))
+
+
+@settings(max_examples=40, deadline=None)
+@given(st.lists(st.integers(0, 3), min_size=36, max_size=36), st.integers(6, 21))
+def test_per_row_block_topk_ties_and_csr_invariants(vals, kb):
+    # per-row reading of TopKBlocks: every row keeps its share by a stable per-row sort
+    nb, b = 6, 4
+    N = nb * b
+    blk = np.array(vals, np.float32).reshape(1, nb, nb)
+    v = np.ones((1, N), np.float32)
+    ix = orc.build_index(v, v, blk, N, b, 4, _bud(k_blocks=kb, block_select=1), override=[BC])
+    rp = ix.rowptr[0]
+    total = 0
+    for R in range(nb):
+        keep = _row_share(kb, nb, R)
+        want = sorted(list(_stable_topk(blk[0, R, :R], keep - 1)) + [R])
+        assert list(ix.blkcols[0, rp[R]:rp[R + 1]]) == want
+        total += keep
+    assert rp[0] == 0 and rp[nb] == total <= kb + nb
+    assert total >= kb                      # shares are rounded up
+    assert (ix.blkcols[0, rp[nb]:] == -1).all()
+
+
+def test_per_row_block_topk_brute_force_and_limits():
+    rng = np.random.default_rng(5)
+    nb, b = 8, 4
+    N = nb * b
+    blk = rng.random((1, nb, nb)).astype(np.float32)
+    v = np.ones((1, N), np.float32)
+    kb = 18                                  # half of the 36 causal blocks
+    ix = orc.build_index(v, v, blk, N, b, 4, _bud(k_blocks=kb, block_select=1), override=[BC])
+    rp = ix.rowptr[0]
+    for R in range(nb):
+        keep = _row_share(kb, nb, R)
+        assert keep == -(-(R + 1) // 2)      # ceil(half of the row's R+1 causal blocks)
+        row = ix.blkcols[0, rp[R]:rp[R + 1]]
+        assert len(row) == keep and row[-1] == R
+        if keep > 1:
+            assert (row[:-1] == _brute_topk(blk[0, R, :R], keep - 1)).all()
+    # k_blocks = nb: 8/36 of every row rounded up; k_blocks = all causal blocks: everything
+    ix = orc.build_index(v, v, blk, N, b, 4, _bud(k_blocks=nb, block_select=1), override=[BC])
+    assert list(np.diff(ix.rowptr[0])) == [1, 1, 1, 1, 2, 2, 2, 2]
+    ix = orc.build_index(v, v, blk, N, b, 4, _bud(k_blocks=36, block_select=1), override=[BC])
+    assert (np.diff(ix.rowptr[0]) == np.arange(1, nb + 1)).all()
+    # the other patterns do not depend on the block rule
+    a = orc.build_index(v, v, blk, N, b, 4, _bud(k_blocks=kb, block_select=0), override=[T])
+    c = orc.build_index(v, v, blk, N, b, 4, _bud(k_blocks=kb, block_select=1), override=[T])
+    assert (a.rowptr == c.rowptr).all() and (a.blkcols[0, :a.rowptr[0, -1]] == c.blkcols[0, :c.rowptr[0, -1]]).all()
+
+
 def test_k_larger_than_candidates_is_clamped():
     N, b = 16, 4
     v = np.arange(16, dtype=np.float32)[None]
