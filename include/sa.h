@@ -133,6 +133,16 @@ sa_status sa_estimate_patterns(sa_ctx *ctx, const void *Q, const void *K, sa_sco
 sa_status sa_build_index(sa_ctx *ctx, sa_scores in, const int32_t *pattern_override_host,
                          sa_index out, void *hip_stream);
 
+/* sa_estimate_patterns followed by sa_build_index as one call: same score
+ * buffers, same index, byte for byte (Alg. 2 l.1-7 on the last-query window,
+ * Alg. 3 l.1-6, and the categorisation of the heads).  The two are interleaved
+ * on the caller's stream and the context's side stream: the selections on v
+ * and s run while the block map is still being computed, and the block
+ * selection runs beside them.  Towards the caller it behaves like a sequence
+ * of kernels on `stream`.  Arguments as in the two calls; errors likewise. */
+sa_status sa_estimate_and_index(sa_ctx *ctx, const void *Q, const void *K, sa_scores scores,
+                                const int32_t *pattern_override_host, sa_index index, void *hip_stream);
+
 /* Alg. 2 / Alg. 3 "Compute Sparse Attention": O[h][i] = sum over the kept
  * keys j of softmax_j(scale * Q_h[i].K[j]) V[j].  Q, O [Hq][N][d]; K, V
  * [Hkv][N][d] bf16 device.  Any index in the documented layout is accepted,

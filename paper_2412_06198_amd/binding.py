@@ -70,6 +70,7 @@ def library():
         lib.sa_set_workspace.argtypes = [vp, vp, C.c_size_t]
         lib.sa_estimate_patterns.argtypes = [vp, vp, vp, SaScores, vp]
         lib.sa_build_index.argtypes = [vp, SaScores, C.POINTER(C.c_int32), SaIndex, vp]
+        lib.sa_estimate_and_index.argtypes = [vp, vp, vp, SaScores, C.POINTER(C.c_int32), SaIndex, vp]
         lib.sa_sparse_prefill.argtypes = [vp, vp, vp, vp, SaIndex, vp, vp]
         lib.sa_sparse_prefill_counted.argtypes = [vp, vp, vp, vp, SaIndex, vp, vp, vp]
         lib.sa_sparse_decode.argtypes = [vp, vp, vp, vp, SaIndex, C.c_int64, vp, vp]
@@ -79,7 +80,8 @@ def library():
         for f in ("sa_default_budgets", "sa_create", "sa_scores_bytes", "sa_index_bytes",
                   "sa_workspace_bytes", "sa_set_workspace", "sa_estimate_patterns",
                   "sa_build_index", "sa_sparse_prefill", "sa_sparse_prefill_counted",
-                  "sa_search_scratch_bytes", "sa_search_patterns", "sa_sparse_decode"):
+                  "sa_search_scratch_bytes", "sa_search_patterns", "sa_sparse_decode",
+                  "sa_estimate_and_index"):
             getattr(lib, f).restype = st
         _lib = lib
     return _lib
@@ -152,6 +154,13 @@ def sa_build_index(ctx, scores: SaScores, pattern_override, index: SaIndex, stre
     if pattern_override is not None:
         ov = (C.c_int32 * len(pattern_override))(*[int(p) for p in pattern_override])
     _check(library().sa_build_index(ctx, scores, ov, index, stream), ctx)
+
+
+def sa_estimate_and_index(ctx, Q, K, scores: SaScores, pattern_override, index: SaIndex, stream=None):
+    ov = None
+    if pattern_override is not None:
+        ov = (C.c_int32 * len(pattern_override))(*[int(p) for p in pattern_override])
+    _check(library().sa_estimate_and_index(ctx, _ptr(Q), _ptr(K), scores, ov, index, stream), ctx)
 
 
 def sa_sparse_prefill(ctx, Q, K, V, index: SaIndex, O, stream=None):
@@ -246,6 +255,9 @@ class Session:
 
     def build_index(self, pattern_override=None):
         sa_build_index(self.ctx, self.scores(), pattern_override, self.index(), self.stream())
+
+    def estimate_and_index(self, Q, K, pattern_override=None):
+        sa_estimate_and_index(self.ctx, Q, K, self.scores(), pattern_override, self.index(), self.stream())
 
     def prefill(self, Q, K, V, O):
         sa_sparse_prefill(self.ctx, Q, K, V, self.index(), O, self.stream())

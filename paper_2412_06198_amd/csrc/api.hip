@@ -230,23 +230,60 @@ sa_status sa_estimate_patterns(sa_ctx *c, const void *Q, const void *K, sa_score
                                            (hipStream_t)stream, c->fork));
 }
 
-sa_status sa_build_index(sa_ctx *c, sa_scores in, const int32_t *override_host, sa_index out,
-                         void *stream) {
-  if (!c) return SA_ERR_INVALID_ARG;
+static sa_status check_index_args(sa_ctx *c, sa_scores in, const int32_t *override_host, sa_index out,
+                                  sa::Override *ov) {
   if (!in.v || !in.s || !in.blk || !out.pattern || !out.n_cols || !out.cols || !out.n_offs ||
       !out.offs || !out.rowptr || !out.blkcols)
     return fail(c, SA_ERR_INVALID_ARG, "null pointer");
   if (((uintptr_t)in.v | (uintptr_t)in.s | (uintptr_t)in.blk) & 15)
     return fail(c, SA_ERR_INVALID_ARG, "v, s, blk must be 16-byte aligned");
-  sa::Override ov;
-  for (int h = 0; h < sa::kMaxHeads; ++h) ov.pat[h] = -1;
+  for (int h = 0; h < sa::kMaxHeads; ++h) ov->pat[h] = -1;
   if (override_host)
     for (int h = 0; h < c->sh.Hq; ++h) {
       const int32_t p = override_host[h];
       if (p < -1 || p > 2) return fail(c, SA_ERR_INVALID_ARG, "pattern override out of range");
-      ov.pat[h] = (int8_t)p;
+      ov->pat[h] = (int8_t)p;
     }
+  return SA_OK;
+}
+
+sa_status sa_build_index(sa_ctx *c, sa_scores in, const int32_t *override_host, sa_index out,
+                         void *stream) {
+  if (!c) return SA_ERR_INVALID_ARG;
+  sa::Override ov;
+  const sa_status s = check_index_args(c, in, override_host, out, &ov);
+  if (s != SA_OK) return s;
   return hip_result(c, sa::launch_build_index(c->sh, c->ws, in, ov, out, (hipStream_t)stream));
+}
+
+sa_status sa_estimate_and_index(sa_ctx *c, const void *Q, const void *K, sa_scores scores,
+                                const int32_t *override_host, sa_index out, void *stream) {
+  if (!c) return SA_ERR_INVALID_ARG;
+  if (!Q || !K) return fail(c, SA_ERR_INVALID_ARG, "null pointer");
+  if (((uintptr_t)Q | (uintptr_t)K) & 15) return fail(c, SA_ERR_INVALID_ARG, "Q, K must be 16-byte aligned");
+  if (!c->have_ws) return fail(c, SA_ERR_INVALID_ARG, "no workspace attached");
+  sa::Override ov;
+  const sa_status s = check_index_args(c, scores, override_host, out, &ov);
+  if (s != SA_OK) return s;
+  hipStream_t st = (hipStream_t)stream;
+  const sa::Fork &fk = c->fork;
+  // Caller's stream: window passes -> selections on v and s; side stream: block means and block
+  // map -> block selection; joined before the pattern decision and the emission.
+  hipError_t e = sa::launch_index_stage(c->sh, c->ws, scores, ov, out, sa::IndexStage::Zero, st);
+  if (e == hipSuccess)
+    e = sa::launch_estimate(c->sh, c->ws, (const uint16_t *)Q, (const uint16_t *)K, scores, st, fk, false);
+  if (e == hipSuccess)
+    e = sa::launch_index_stage(c->sh, c->ws, scores, ov, out, sa::IndexStage::ColumnsDiagonals, st);
+  if (e == hipSuccess)
+    e = sa::launch_index_stage(c->sh, c->ws, scores, ov, out, sa::IndexStage::Blocks, fk.aux ? fk.aux : st);
+  if (fk.aux) {
+    // join even after an error above, so that the side stream never outlives the call unjoined
+    hipError_t j = hipEventRecord(fk.join, fk.aux);
+    if (j == hipSuccess) j = hipStreamWaitEvent(st, fk.join, 0);
+    if (e == hipSuccess) e = j;
+  }
+  if (e == hipSuccess) e = sa::launch_index_stage(c->sh, c->ws, scores, ov, out, sa::IndexStage::Emit, st);
+  return hip_result(c, e);
 }
 
 static sa_status prefill_common(sa_ctx *c, const void *Q, const void *K, const void *V, sa_index idx,

@@ -611,14 +611,17 @@ __global__ __launch_bounds__(64 * kMapWaves, (MT <= 8 ? 4 : 2)) void block_map_k
 }  // namespace
 
 hipError_t launch_estimate(const Shape &sh, const Workspace &ws, const uint16_t *Q,
-                           const uint16_t *K, sa_scores out, hipStream_t st, const Fork &fk) {
+                           const uint16_t *K, sa_scores out, hipStream_t st, const Fork &fk,
+                           bool join_back) {
   const float c = sh.scale * kLog2e;
   float *bias = (float *)ws.stats;
   // Two chains with complementary limits run side by side: the Q chain (block means of Q: HBM
   // bandwidth; block map: latency of many small L2 reads) on the context's side stream, the K
   // chain (both window passes: exp and vector ALU work on a quarter of the bytes) on the caller's
   // stream.  The side stream forks from the caller's stream at entry and joins it at exit, so
-  // towards the caller the call behaves like a sequence of kernels on the given stream.
+  // towards the caller the call behaves like a sequence of kernels on the given stream
+  // (join_back == false: the caller of this function goes on using both streams and joins them
+  // itself).
   hipStream_t sq = st;
   hipError_t e;
   if (fk.aux) {
@@ -646,7 +649,7 @@ hipError_t launch_estimate(const Shape &sh, const Workspace &ws, const uint16_t 
     block_map_kernel<32><<<bgrid, 64 * kMapWaves, 0, sq>>>(ws.qblk, ws.kblk, sh, c, out.blk);
   window_stats_reduce_kernel<<<dim3(sh.Hq, kWin / 16), 1024, 0, st>>>(ws.part, sh.nchunks, sh.w, bias);
   window_scores_kernel<<<wgrid, 256, 0, st>>>(Q, K, sh, c, bias, out.v, out.s);
-  if (fk.aux) {
+  if (fk.aux && join_back) {
     if ((e = hipEventRecord(fk.join, fk.aux)) != hipSuccess) return e;
     if ((e = hipStreamWaitEvent(st, fk.join, 0)) != hipSuccess) return e;
   }

@@ -59,6 +59,9 @@ struct IdxArgs {
   sa_index out;
   int P, PW, seg;                  // workgroups per head, wave parts per head, keys of v / s per wave part
   int ksel[NSEL];                  // clamped k of every selection
+  // Which part of the work a launch does: bit 0 = the selections on v and s, bit 1 = the selection
+  // on the block map (the two parts touch disjoint fields of the scratch and may run side by side).
+  int mask;
 };
 
 // floor(x * 2^30) of a finite fp32 x >= 0 given by its bits.
@@ -246,6 +249,8 @@ __global__ __launch_bounds__(BT) void idx_hist_kernel(IdxArgs a) {
   const int p = blockIdx.x, h = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int N = sh.N, nb = sh.nb;
   IdxScratch *G = a.scratch + h;
+  const bool do_vs = a.mask & 1, do_blk = (a.mask & 2) && a.ksel[4] > 0;
+  if (!do_vs && !do_blk) return;
   const unsigned *vb = a.v + (size_t)h * N, *sb = a.s + (size_t)h * N;
   const unsigned *bb = a.blk + (size_t)h * nb * nb;
   for (int i = tid; i < NH * BINS; i += BT) (&hist[0][0])[i] = 0u;
@@ -285,7 +290,7 @@ __global__ __launch_bounds__(BT) void idx_hist_kernel(IdxArgs a) {
       }
     }
   };
-  wave_visit4(vb, lo, hi, true, [&](const Keys4 &v, int i0, int lim) {
+  if (do_vs) wave_visit4(vb, lo, hi, true, [&](const Keys4 &v, int i0, int lim) {
     visit(v, i0, lim, 0);
     if (LEVEL == 1) {
 #pragma unroll
@@ -297,8 +302,8 @@ __global__ __launch_bounds__(BT) void idx_hist_kernel(IdxArgs a) {
         }
     }
   });
-  wave_visit4(sb, lo, hi, true, [&](const Keys4 &v, int i0, int lim) { visit(v, i0, lim, 1); });
-  if (act[4])
+  if (do_vs) wave_visit4(sb, lo, hi, true, [&](const Keys4 &v, int i0, int lim) { visit(v, i0, lim, 1); });
+  if (do_blk)
     wave_rows_visit4(bb, nb, gw, a.PW, (nb & 3) == 0, [](int) {},
                      [&](const Keys4 &v, int i0, int lim) { visit(v, i0, lim, 2); }, [](int) {});
   if (LEVEL == 1) {
@@ -311,7 +316,7 @@ __global__ __launch_bounds__(BT) void idx_hist_kernel(IdxArgs a) {
     const unsigned c = (&hist[0][0])[i];
     if (c) atomicAdd(&gh[i], c);
   }
-  if (LEVEL == 1 && tid == 0) {
+  if (LEVEL == 1 && do_vs && tid == 0) {
     unsigned long long tv = 0, tc = 0;
     for (int w = 0; w < WPB; ++w) { tv += red64[0][w]; tc += red64[1][w]; }
     atomicAdd(&G->vtot, tv);
@@ -332,6 +337,7 @@ __global__ __launch_bounds__(BT) void idx_select_kernel(IdxArgs a) {
     *(uint4 *)&(&hist[0][0])[i] = *(const uint4 *)&gh[i];
   __syncthreads();
   for (int q = wv; q < NSEL; q += WPB) {  // wave w takes selections w and w + 4
+    if (!(a.mask & (q < 4 ? 1 : 2))) continue;
     if (a.ksel[q] <= 0) {
       if (LEVEL == 3 && lane == 0) { G->thr[q] = 0xFFFFFFFFu; G->need[q] = 0u; }
       continue;
@@ -370,7 +376,8 @@ __global__ __launch_bounds__(BT) void idx_count_kernel(IdxArgs a) {
   for (int q = 0; q < NSEL; ++q) { thr[q] = G->thr[q]; need[q] = G->need[q]; }
   const int gw = p * WPB + wv;
   const int lo = min(gw * a.seg, N), hi = min(lo + a.seg, N);
-  for (int arr = 0; arr < 2; ++arr) {
+  const bool do_vs = a.mask & 1;
+  for (int arr = 0; arr < 2 && do_vs; ++arr) {
     unsigned gt = 0, eq = 0;
     unsigned long long ts = 0;
     const unsigned tp = thr[arr], tk = thr[arr + 2];
@@ -388,7 +395,7 @@ __global__ __launch_bounds__(BT) void idx_count_kernel(IdxArgs a) {
     }
     if (lane == 0) { G->wgt[arr][gw] = gt; G->weq[arr][gw] = eq; red64[arr][wv] = ts; }
   }
-  if (!sh.row_select) {
+  if (!sh.row_select && (a.mask & 2)) {
     unsigned gt = 0, eq = 0;
     wave_rows_visit4(
         bb, nb, gw, a.PW, (nb & 3) == 0, [&](int) { gt = 0; eq = 0; },
@@ -406,11 +413,43 @@ __global__ __launch_bounds__(BT) void idx_count_kernel(IdxArgs a) {
         });
   }
   __syncthreads();
-  if (tid < 2) {
+  if (tid < 2 && do_vs) {
     unsigned long long t = 0;
     for (int w = 0; w < WPB; ++w) t += red64[tid][w];
     atomicAdd(&G->topsum[tid], t);
   }
+}
+
+// Pattern of head h: the caller's override, else the integer lift tests on the sums that the level-1
+// histogram launch (vtot, ct) and the counting launch (topsum) left in the scratch.
+__device__ inline int decide_pattern(const IdxArgs &a, const IdxScratch *G, int h) {
+  const Shape &sh = a.sh;
+  const int N = sh.N, nb = sh.nb;
+  int pat = a.ov.pat[h];
+  if (pat >= 0) return pat;
+  long long sbnd = (long long)sh.sink * sh.b;
+  if (sbnd > N) sbnd = N;
+  long long lb0 = (long long)(nb - sh.local) * sh.b;
+  if (lb0 < sbnd) lb0 = sbnd;
+  unsigned long long E = 0, ET = 0;
+  for (int i = 0; i < sh.w; ++i) {
+    const long long qi1 = (long long)N - sh.w + i + 1;
+    E += (unsigned long long)qi1;
+    ET += (unsigned long long)(qi1 < sbnd ? qi1 : sbnd);
+    if (qi1 > lb0) ET += (unsigned long long)(qi1 - lb0);
+  }
+  const unsigned long long vt = G->vtot, ct = G->ct;
+  typedef unsigned __int128 u128;
+  if ((u128)sh.lift_den * ct * E >= (u128)sh.lift_num * vt * ET) return SA_TRIANGULAR;
+  // sum over the probe best = sum over keys above the threshold + ties at the threshold
+  const unsigned long long sv =
+      a.ksel[0] > 0 ? G->topsum[0] + (unsigned long long)G->need[0] * fx30(G->thr[0]) : 0ull;
+  const unsigned long long ss =
+      a.ksel[1] > 0 ? G->topsum[1] + (unsigned long long)G->need[1] * fx30(G->thr[1]) : 0ull;
+  if ((u128)sh.lift_den * (sv + ss) * E >=
+      (u128)sh.lift_num * vt * (unsigned long long)(sh.probe_v + sh.probe_s) * (unsigned long long)sh.w)
+    return SA_INTERVAL_SLASH;
+  return SA_BLOCK_CLUSTER;
 }
 
 // One workgroup per head: pattern decision, prefixes of the per-part and per-row counts, rowptr.
@@ -425,38 +464,9 @@ __global__ __launch_bounds__(BT) void idx_scan_kernel(IdxArgs a) {
   unsigned thr[NSEL], need[NSEL];
 #pragma unroll
   for (int q = 0; q < NSEL; ++q) { thr[q] = G->thr[q]; need[q] = G->need[q]; }
-  // ---- pattern of the head (caller's override, else the integer lift tests) --------------------
+  // ---- pattern of the head --------------------------------------------------------------------------
   if (tid == 0) {
-    int pat = a.ov.pat[h];
-    if (pat < 0) {
-      long long sbnd = (long long)sh.sink * sh.b;
-      if (sbnd > N) sbnd = N;
-      long long lb0 = (long long)(nb - sh.local) * sh.b;
-      if (lb0 < sbnd) lb0 = sbnd;
-      unsigned long long E = 0, ET = 0;
-      for (int i = 0; i < sh.w; ++i) {
-        const long long qi1 = (long long)N - sh.w + i + 1;
-        E += (unsigned long long)qi1;
-        ET += (unsigned long long)(qi1 < sbnd ? qi1 : sbnd);
-        if (qi1 > lb0) ET += (unsigned long long)(qi1 - lb0);
-      }
-      const unsigned long long vt = G->vtot, ct = G->ct;
-      typedef unsigned __int128 u128;
-      if ((u128)sh.lift_den * ct * E >= (u128)sh.lift_num * vt * ET) {
-        pat = SA_TRIANGULAR;
-      } else {
-        // sum over the probe best = sum over keys above the threshold + ties at the threshold
-        const unsigned long long sv =
-            a.ksel[0] > 0 ? G->topsum[0] + (unsigned long long)need[0] * fx30(thr[0]) : 0ull;
-        const unsigned long long ss =
-            a.ksel[1] > 0 ? G->topsum[1] + (unsigned long long)need[1] * fx30(thr[1]) : 0ull;
-        if ((u128)sh.lift_den * (sv + ss) * E >=
-            (u128)sh.lift_num * vt * (unsigned long long)(sh.probe_v + sh.probe_s) * (unsigned long long)sh.w)
-          pat = SA_INTERVAL_SLASH;
-        else
-          pat = SA_BLOCK_CLUSTER;
-      }
-    }
+    const int pat = decide_pattern(a, G, h);
     G->pattern = pat;
     a.out.pattern[h] = pat;
     s_pat = pat;
@@ -648,8 +658,9 @@ __global__ __launch_bounds__(BT) void idx_emit_rows_kernel(IdxArgs a) {
 
 size_t index_scratch_bytes(int n_heads) { return sizeof(IdxScratch) * (size_t)n_heads; }
 
-hipError_t launch_build_index(const Shape &sh, const Workspace &ws, sa_scores in, const Override &ov,
-                              sa_index out, hipStream_t st) {
+namespace {
+
+IdxArgs index_args(const Shape &sh, const Workspace &ws, sa_scores in, const Override &ov, sa_index out) {
   IdxArgs a;
   a.v = (const unsigned *)in.v; a.s = (const unsigned *)in.s; a.blk = (const unsigned *)in.blk;
   a.scratch = (IdxScratch *)ws.idx;
@@ -668,21 +679,64 @@ hipError_t launch_build_index(const Shape &sh, const Workspace &ws, sa_scores in
   a.ksel[2] = sh.k_v < sh.N ? sh.k_v : sh.N;
   a.ksel[3] = sh.k_s < sh.N ? sh.k_s : sh.N;
   a.ksel[4] = sh.row_select ? 0 : (int)kb;   // per-row rule: selected row by row while emitting
-  const dim3 grid(P, sh.Hq);
-  idx_zero_kernel<<<sh.Hq, 256, 0, st>>>(a.scratch);
+  a.mask = 3;
+  return a;
+}
+
+void launch_levels(const IdxArgs &a, hipStream_t st) {
+  const dim3 grid(a.P, a.sh.Hq);
   idx_hist_kernel<1><<<grid, BT, 0, st>>>(a);
-  idx_select_kernel<1><<<sh.Hq, BT, 0, st>>>(a);
+  idx_select_kernel<1><<<a.sh.Hq, BT, 0, st>>>(a);
   idx_hist_kernel<2><<<grid, BT, 0, st>>>(a);
-  idx_select_kernel<2><<<sh.Hq, BT, 0, st>>>(a);
+  idx_select_kernel<2><<<a.sh.Hq, BT, 0, st>>>(a);
   idx_hist_kernel<3><<<grid, BT, 0, st>>>(a);
-  idx_select_kernel<3><<<sh.Hq, BT, 0, st>>>(a);
+  idx_select_kernel<3><<<a.sh.Hq, BT, 0, st>>>(a);
   idx_count_kernel<<<grid, BT, 0, st>>>(a);
-  idx_scan_kernel<<<sh.Hq, BT, 0, st>>>(a);
+}
+
+void launch_finish(const IdxArgs &a, hipStream_t st) {
+  const dim3 grid(a.P, a.sh.Hq);
+  idx_scan_kernel<<<a.sh.Hq, BT, 0, st>>>(a);
   idx_emit_kernel<<<grid, BT, 0, st>>>(a);
-  if (sh.row_select) {
-    if (sh.nb <= 256) idx_emit_rows_kernel<4><<<grid, BT, 0, st>>>(a);
-    else if (sh.nb <= 1024) idx_emit_rows_kernel<16><<<grid, BT, 0, st>>>(a);
+  if (a.sh.row_select) {
+    if (a.sh.nb <= 256) idx_emit_rows_kernel<4><<<grid, BT, 0, st>>>(a);
+    else if (a.sh.nb <= 1024) idx_emit_rows_kernel<16><<<grid, BT, 0, st>>>(a);
     else idx_emit_rows_kernel<kMaxNb / 64><<<grid, BT, 0, st>>>(a);
+  }
+}
+
+}  // namespace
+
+hipError_t launch_build_index(const Shape &sh, const Workspace &ws, sa_scores in, const Override &ov,
+                              sa_index out, hipStream_t st) {
+  const IdxArgs a = index_args(sh, ws, in, ov, out);
+  idx_zero_kernel<<<sh.Hq, 256, 0, st>>>(a.scratch);
+  launch_levels(a, st);
+  launch_finish(a, st);
+  return hipGetLastError();
+}
+
+// The same work in parts, so that it can run beside the estimator: the selections on v and s as
+// soon as the window passes are done, the block-map selection as soon as the block map is (on
+// another stream), and the emission once both are.
+hipError_t launch_index_stage(const Shape &sh, const Workspace &ws, sa_scores in, const Override &ov,
+                              sa_index out, IndexStage stage, hipStream_t st) {
+  IdxArgs a = index_args(sh, ws, in, ov, out);
+  switch (stage) {
+    case IndexStage::Zero:
+      idx_zero_kernel<<<sh.Hq, 256, 0, st>>>(a.scratch);
+      break;
+    case IndexStage::ColumnsDiagonals:
+      a.mask = 1;
+      launch_levels(a, st);
+      break;
+    case IndexStage::Blocks:
+      a.mask = 2;
+      if (!sh.row_select) launch_levels(a, st);
+      break;
+    case IndexStage::Emit:
+      launch_finish(a, st);
+      break;
   }
   return hipGetLastError();
 }

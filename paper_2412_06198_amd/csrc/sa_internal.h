@@ -46,6 +46,9 @@ size_t index_scratch_bytes(int n_heads);
 // everything is enqueued on the caller's stream.
 struct Fork { hipStream_t aux; hipEvent_t fork, mid, join; };
 
+// Parts of the index builder when it runs interleaved with the estimator.
+enum class IndexStage { Zero, ColumnsDiagonals, Blocks, Emit };
+
 }  // namespace sa
 
 // The context behind the opaque handle of the C ABI (host memory).
@@ -63,9 +66,12 @@ struct sa_ctx {
 namespace sa {
 
 hipError_t launch_estimate(const Shape &sh, const Workspace &ws, const uint16_t *Q,
-                           const uint16_t *K, sa_scores out, hipStream_t st, const Fork &fk);
+                           const uint16_t *K, sa_scores out, hipStream_t st, const Fork &fk,
+                           bool join_back = true);
 hipError_t launch_build_index(const Shape &sh, const Workspace &ws, sa_scores in,
                               const Override &ov, sa_index out, hipStream_t st);
+hipError_t launch_index_stage(const Shape &sh, const Workspace &ws, sa_scores in, const Override &ov,
+                              sa_index out, IndexStage stage, hipStream_t st);
 size_t decode_partial_bytes(const Shape &sh);
 hipError_t launch_sparse_decode(const Shape &sh, const Workspace &ws, const uint16_t *q, const uint16_t *K,
                                 const uint16_t *V, sa_index idx, int pos, uint16_t *o, hipStream_t st);

@@ -91,3 +91,30 @@ def test_pattern_rule_boundary_on_gpu():
     want = orc.build_index(v, s, blk, N, b, w, bud)
     assert got.pattern[0] == T and got.pattern[1] != T
     assert_index_equal(got, want)
+
+
+@pytest.mark.parametrize("N,b,keep,rows", [(4096, 64, 0.10, 0), (2048, 128, 0.3, 1), (8192 + 128, 128, 0.07, 0),
+                                           (1024, 64, 0.5, 1)])
+def test_one_call_estimate_and_index_is_byte_identical(N, b, keep, rows):
+    # sa_estimate_and_index against sa_estimate_patterns + sa_build_index: same scores, same index
+    print(f"case one-call N={N} b={b} rows={rows}", flush=True)
+    Hq, Hkv = 8, 2
+    wl = gen.scaled(gen.WORKLOADS["cfg3"], name="t", n_q_heads=Hq, n_kv_heads=Hkv, seq_len=N,
+                    block=b, seed=N + 3, n_hot=4, hot_block=b, keep=keep)
+    data = gen.generate(wl)
+    bud = orc.default_budgets(N, b, keep)
+    bud.block_select = rows
+    Q, K = dev_bf16(data["Q"]), dev_bf16(data["K"])
+    two, one = make_session(Hq, Hkv, N, b, 64, bud), make_session(Hq, Hkv, N, b, 64, bud)
+    for ov in (None, [T, IS, BC, IS, BC, T, IS, BC], [BC] * Hq, None):
+        two.estimate(Q, K)
+        two.build_index(ov)
+        for t in one.index_tensors() + [one.v, one.s, one.blk]:
+            t.fill_(-7)                      # stale contents must not survive
+        one.estimate_and_index(Q, K, ov)
+        for a, c in zip(download_scores(two), download_scores(one)):
+            assert a.tobytes() == c.tobytes()
+        want = download_index(two)
+        assert_index_equal(download_index(one), want)
+    v, s, blk = download_scores(one)
+    assert_index_equal(download_index(one), orc.build_index(v, s, blk, N, b, 64, bud))

@@ -88,6 +88,26 @@ def test_longest_supported_sequence_256k():
     _whole_path("max256k", 40, wl=wl)
 
 
+def test_cfg5_one_call_estimate_and_index():
+    # the launch configuration bench.py times: scores and index of the one-call form against the
+    # two calls, byte for byte, at the benchmark size
+    print("case cfg5 one-call", flush=True)
+    wl = gen.WORKLOADS["cfg5"]
+    data = gen.generate(wl)
+    N, b, w, Hq = wl.seq_len, wl.block, wl.last_q, wl.n_q_heads
+    Q, K = dev_bf16(data["Q"]), dev_bf16(data["K"])
+    two = sa.Session(Hq, wl.n_kv_heads, N, b, w, keep=wl.keep)
+    one = sa.Session(Hq, wl.n_kv_heads, N, b, w, keep=wl.keep)
+    two.estimate(Q, K)
+    two.build_index(None)
+    for rep in range(3):
+        one.estimate_and_index(Q, K, None)
+        for a, c in zip(download_scores(two), download_scores(one)):
+            assert a.tobytes() == c.tobytes()
+        assert_index_equal(download_index(one), download_index(two))
+    assert len(set(download_index(one).pattern.tolist())) == 3
+
+
 def test_counters_match_oracle_mask_count():
     print("case counters", flush=True)
     Hq, Hkv, N, b, w = 4, 2, 1024, 64, 64
