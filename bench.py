@@ -53,7 +53,8 @@ def cpu_baseline(orc, data, wl, bud, sample_rows):
     }
 
 
-def run_workload(name, steps, warmup, layers, with_cpu, sample_rows, with_dense=False, block_select=0):
+def run_workload(name, steps, warmup, layers, with_cpu, sample_rows, with_dense=False, block_select=0,
+                 diagonal_select=0):
     import numpy as np
     import torch
 
@@ -63,7 +64,7 @@ def run_workload(name, steps, warmup, layers, with_cpu, sample_rows, with_dense=
     wl = gen.WORKLOADS[name]
     N, b, w, Hq, Hkv, d = wl.seq_len, wl.block, wl.last_q, wl.n_q_heads, wl.n_kv_heads, wl.head_dim
     dev = torch.device("cuda:0")
-    ses = sa.Session(Hq, Hkv, N, b, w, keep=wl.keep, block_select=block_select)
+    ses = sa.Session(Hq, Hkv, N, b, w, keep=wl.keep, block_select=block_select, diagonal_select=diagonal_select)
 
     def up(bits):
         return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(dev)
@@ -188,6 +189,7 @@ def run_workload(name, steps, warmup, layers, with_cpu, sample_rows, with_dense=
         from oracle import oracle as orc
         bud = orc.default_budgets(N, b, wl.keep)
         bud.block_select = block_select
+        bud.diagonal_select = diagonal_select
         res["cpu_baseline"] = cpu_baseline(orc, first, wl, bud, sample_rows)
         log(f"[{name}] cpu_baseline {res['cpu_baseline']}")
     ses.close()
@@ -440,6 +442,8 @@ def main():
     ap.add_argument("--block-select", choices=("global", "row"), default="global",
                     help="how Block-Cluster heads spend k_blocks: one top-k (Alg. 3 read literally) or the same "
                          "fraction of every row block")
+    ap.add_argument("--diagonals", choices=("exact", "blocks"), default="exact",
+                    help="selected diagonals of Interval-Slash heads element-exact (default) or widened to whole blocks")
     ap.add_argument("--block-rules", action="store_true",
                     help="compare the two block rules (time, kept pairs, error against all-keys attention) instead")
     ap.add_argument("--decode", action="store_true",
@@ -477,12 +481,13 @@ def main():
         run_search(a.search, not a.no_cpu_baseline)
         return
     bsel = 1 if a.block_select == "row" else 0
+    dsel = 1 if a.diagonals == "blocks" else 0
     main_res = run_workload(a.workload, a.steps, a.warmup, a.layers, not a.no_cpu_baseline, a.sample_rows,
-                            block_select=bsel)
+                            block_select=bsel, diagonal_select=dsel)
     also = None
     if a.also and a.also != a.workload:
         also = run_workload(a.also, max(a.steps, 20), a.warmup, min(a.layers, 2), False, a.sample_rows,
-                            with_dense=True, block_select=bsel)
+                            with_dense=True, block_select=bsel, diagonal_select=dsel)
 
     traffic = None
     tp = os.path.join(ROOT, "profiles", f"traffic_{a.workload}.json")
@@ -500,7 +505,8 @@ def main():
         "config": {"workload": f"{a.workload}: Hq={wl.n_q_heads} Hkv={wl.n_kv_heads} d={wl.head_dim} "
                                f"N={wl.seq_len} block={wl.block} last_q={wl.last_q} keep={wl.keep} "
                                f"layers={a.layers} (seeds {wl.seed}..{wl.seed + a.layers - 1}), patterns chosen at run time"
-                               + (", blocks chosen per row" if bsel else "")},
+                               + (", blocks chosen per row" if bsel else "")
+                               + (", diagonals widened to blocks" if dsel else "")},
         "roofline": {"bound": "mfma", "kernel": "sparse_prefill_kernel",
                      "achieved": round(main_res["tflops"]["kept"], 2), "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(main_res["tflops"]["kept"] / PEAK_BF16_TFLOPS, 4),

@@ -69,6 +69,14 @@ typedef enum {
  *                      i.e. the same fraction of every row (at most nb blocks above k_blocks). */
 typedef enum { SA_BLOCKS_GLOBAL = 0, SA_BLOCKS_PER_ROW = 1 } sa_block_select;
 
+/* Granularity of the selected diagonals of an Interval-Slash head (Alg. 2 combines vertical and
+ * slash indices but does not say at which granularity the kernel applies them):
+ *   SA_DIAGONALS_EXACT   query i attends key i - o for every selected offset o (element-exact);
+ *   SA_DIAGONALS_BLOCKS  every block pair (i / block, (i - o) / block) is kept whole: the offsets
+ *                        become part of the block CSR (at most two key blocks per offset and row
+ *                        block) and the offs list of the index comes back empty (n_offs = 0). */
+typedef enum { SA_DIAGONALS_EXACT = 0, SA_DIAGONALS_BLOCKS = 1 } sa_diagonal_select;
+
 typedef struct {
   int32_t n_q_heads, n_kv_heads, head_dim; /* n_q_heads % n_kv_heads == 0, <= 128 heads; head_dim must be 128 */
   int32_t seq_len, block, last_q;          /* seq_len % block == 0; block in {64,128}; 1 <= last_q <= 64 */
@@ -79,6 +87,7 @@ typedef struct {
   int64_t q_head_stride, q_row_stride;     /* in elements; 0 => contiguous [H][N][d]; O uses Q's strides */
   int64_t kv_head_stride, kv_row_stride;   /* K and V; row strides must be multiples of 8 elements */
   int32_t block_select;                    /* sa_block_select; 0 => SA_BLOCKS_GLOBAL */
+  int32_t diagonal_select;                 /* sa_diagonal_select; 0 => SA_DIAGONALS_EXACT */
 } sa_config;
 
 /* Device score buffers written by sa_estimate_patterns (Alg. 2 SumRows /

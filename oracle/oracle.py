@@ -52,6 +52,7 @@ class Budgets:
     lift_num: int = 4
     lift_den: int = 1
     block_select: int = 0   # 0: one global top-k over the block map, 1: the same fraction of every row
+    diagonal_select: int = 0  # 0: element-exact diagonals, 1: every selected diagonal widened to blocks
 
 
 @dataclass
@@ -146,8 +147,13 @@ def default_budgets(N, b, rho) -> Budgets:
 
 def block_capacity(N, b, bud: Budgets):
     # the per-row rule rounds every row's share up: at most one block per row above k_blocks
-    kb = bud.k_blocks + (N // b if bud.block_select == 1 else 0)
-    return max(kb, triangular_count(N // b, bud.sink_blocks, bud.local_blocks))
+    nb = N // b
+    kb = bud.k_blocks + (nb if bud.block_select == 1 else 0)
+    cap = max(kb, triangular_count(nb, bud.sink_blocks, bud.local_blocks))
+    if bud.diagonal_select == 1:
+        # a diagonal touches at most two key blocks per row block
+        cap = max(cap, sum(min(R + 1, 2 * min(bud.k_slash, N) + 1) for R in range(nb)))
+    return cap
 
 
 def build_index(v, s, blk, N, b, w, bud: Budgets, override=None) -> Index:
@@ -170,7 +176,7 @@ def build_index(v, s, blk, N, b, w, bud: Budgets, override=None) -> Index:
                                   bud.lift_num, bud.lift_den, _p(override, i32), cap,
                                   _p(idx.pattern, i32), _p(idx.n_cols, i32), _p(idx.cols, i32),
                                   _p(idx.n_offs, i32), _p(idx.offs, i32), _p(idx.rowptr, i32),
-                                  _p(idx.blkcols, i32), bud.block_select)
+                                  _p(idx.blkcols, i32), bud.block_select, bud.diagonal_select)
     assert rc == 0
     return idx
 

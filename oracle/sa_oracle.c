@@ -368,15 +368,20 @@ static int choose_pattern(const float *v, const float *s, int N, int b, int w, i
  * flattened causal off-diagonal entries.  block_select 1 (the per-row reading of
  * the same step): row R keeps keep(R) = min(R+1, ceil(k_blocks (R+1) / (nb (nb+1)/2)))
  * blocks: its diagonal block and the keep(R)-1 largest blk[R][C], C<R (ties to
- * the lower C), i.e. every row block gets the same fraction of its causal blocks. */
+ * the lower C), i.e. every row block gets the same fraction of its causal blocks.
+ * diagonal_select 1 (diagonals at block granularity instead of element-exact):
+ * an Interval-Slash head keeps, for every selected offset o and every query i >= o,
+ * the whole block pair (i / b, (i - o) / b); the offsets are then part of the CSR
+ * and the offs list is returned empty (n_offs = 0). */
 int oracle_build_index(const float *v, const float *s, const float *blk, int Hq, int N, int b,
                        int w, int sink_blocks, int local_blocks, int k_vertical, int k_slash,
                        int k_blocks, int probe_v, int probe_s, int lift_num, int lift_den,
                        const int32_t *override, int cap_b, int32_t *pattern, int32_t *n_cols,
                        int32_t *cols, int32_t *n_offs, int32_t *offs, int32_t *rowptr,
-                       int32_t *blkcols, int block_select) {
+                       int32_t *blkcols, int block_select, int diagonal_select) {
   if (N % b) return 1;
   if (block_select != 0 && block_select != 1) return 1;
+  if (diagonal_select != 0 && diagonal_select != 1) return 1;
   const int nb = N / b;
   int err = 0;
 #pragma omp parallel for schedule(dynamic, 1)
@@ -402,6 +407,12 @@ int oracle_build_index(const float *v, const float *s, const float *blk, int Hq,
     /* block CSR */
     unsigned char *keep = (unsigned char *)calloc((size_t)nb * nb, 1);
     for (int R = 0; R < nb; ++R) keep[(size_t)R * nb + R] = 1;
+    if (pat == PAT_INTERVAL_SLASH && diagonal_select == 1) {
+      for (int t = 0; t < n_offs[h]; ++t)
+        for (int i = oh[t]; i < N; ++i) keep[(size_t)(i / b) * nb + (i - oh[t]) / b] = 1;
+      for (int t = 0; t < k_slash; ++t) oh[t] = -1;
+      n_offs[h] = 0;
+    }
     if (pat == PAT_TRIANGULAR) {
       for (int R = 0; R < nb; ++R)
         for (int C = 0; C <= R; ++C)

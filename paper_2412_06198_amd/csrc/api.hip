@@ -92,6 +92,7 @@ sa_status sa_create(const sa_config *cfg, sa_ctx **out) {
   if (cfg->probe_v < 0 || cfg->probe_s < 0 || cfg->lift_num < 0 || cfg->lift_den < 0) return SA_ERR_INVALID_ARG;
   if (cfg->softmax_scale < 0.f) return SA_ERR_INVALID_ARG;
   if (cfg->block_select != SA_BLOCKS_GLOBAL && cfg->block_select != SA_BLOCKS_PER_ROW) return SA_ERR_INVALID_ARG;
+  if (cfg->diagonal_select != SA_DIAGONALS_EXACT && cfg->diagonal_select != SA_DIAGONALS_BLOCKS) return SA_ERR_INVALID_ARG;
 
   sa_ctx *c = new (std::nothrow) sa_ctx();
   if (!c) return SA_ERR_INVALID_ARG;
@@ -109,7 +110,14 @@ sa_status sa_create(const sa_config *cfg, sa_ctx **out) {
   s.row_select = cfg->block_select == SA_BLOCKS_PER_ROW;
   // the per-row rule rounds every row's share up: at most one block per row above k_b
   const long long kcap = (long long)s.k_b + (s.row_select ? nb : 0);
-  const long long cap = tri > kcap ? tri : kcap;
+  long long cap = tri > kcap ? tri : kcap;
+  s.diag_blocks = cfg->diagonal_select == SA_DIAGONALS_BLOCKS;
+  if (s.diag_blocks) {
+    // a diagonal touches at most two key blocks per row block: row R holds min(R + 1, 2 k_s + 1)
+    const long long ks = s.k_s < s.N ? s.k_s : s.N, m = 2 * ks + 1;
+    const long long dcap = m >= nb ? (long long)nb * (nb + 1) / 2 : m * (m + 1) / 2 + (nb - m) * m;
+    if (dcap > cap) cap = dcap;
+  }
   if (cap > 0x7FFFFFFFll) { delete c; return SA_ERR_UNSUPPORTED; }
   s.cap_b = (int)cap;
   s.nchunks = (s.N + sa::kChunk - 1) / sa::kChunk;

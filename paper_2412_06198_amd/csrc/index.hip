@@ -21,6 +21,10 @@
 // same fraction of its causal blocks) the fifth selection is switched off and
 // one more launch selects inside each row instead: one wave per row, keys in
 // registers, the threshold found bit by bit.
+//
+// With block-granular diagonals four launches after the emission turn the selected
+// offsets of the Interval-Slash heads into rows of the block CSR (bitmap per row,
+// count, prefix, ordered write) and empty the offset list.
 #include <cstddef>
 
 #include "sa_internal.h"
@@ -654,6 +658,104 @@ __global__ __launch_bounds__(BT) void idx_emit_rows_kernel(IdxArgs a) {
     emit_row_select<T>(hb + (size_t)R * nb, R, row_share(sh, R) - 1, bc + rp[R]);
 }
 
+// ---- diagonals at block granularity -----------------------------------------------------------------
+// Interval-Slash heads when the selected diagonals are kept as whole blocks.  Runs after the
+// emission, which has left the selected offsets in the index: one wave per row block R collects the
+// key blocks that hold a key i - o of a query i of the row (at most two per offset) and the diagonal
+// block in a bitmap (the wave's own LDS slice).  PASS 0 stores the number of blocks of the row,
+// PASS 1 writes them in ascending order behind the row pointer.
+template <int PASS>
+__global__ __launch_bounds__(BT) void idx_diag_rows_kernel(IdxArgs a) {
+  __shared__ unsigned bm[WPB][kMaxNb / 32];
+  const Shape &sh = a.sh;
+  const int h = blockIdx.y, nb = sh.nb, lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  IdxScratch *G = a.scratch + h;
+  if (G->pattern != SA_INTERVAL_SLASH) return;
+  const int gw = blockIdx.x * WPB + wv;
+  const int n_offs = a.out.n_offs[h];
+  const int32_t *offs = a.out.offs + (size_t)h * sh.k_s;
+  const int32_t *rp = a.out.rowptr + (size_t)h * (nb + 1);
+  int32_t *bc = a.out.blkcols + (size_t)h * sh.cap_b;
+  const int shift = sh.b == 128 ? 7 : 6;
+  unsigned *w = bm[wv];
+  for (int R = gw; R < nb; R += a.PW) {
+    const int words = (R >> 5) + 1;  // bits 0..R
+    for (int i = lane; i < words; i += 64) w[i] = 0u;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    const long long first = (long long)R << shift, last = first + sh.b - 1;  // queries of the row
+    for (int t = lane; t < n_offs; t += 64) {
+      const long long o = offs[t];
+      if (last - o < 0) continue;  // the diagonal starts below this row
+      const int c0 = (int)((first - o > 0 ? first - o : 0) >> shift), c1 = (int)((last - o) >> shift);
+      atomicOr(&w[c0 >> 5], 1u << (c0 & 31));
+      if (c1 != c0) atomicOr(&w[c1 >> 5], 1u << (c1 & 31));
+    }
+    if (lane == 0) atomicOr(&w[R >> 5], 1u << (R & 31));
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    int run = PASS == 1 ? rp[R] : 0;
+    for (int i0 = 0; i0 < words; i0 += 64) {
+      unsigned bits = i0 + lane < words ? w[i0 + lane] : 0u;
+      const int pc = __popc(bits);
+      int incl = pc;  // inclusive prefix over the lanes
+      for (int d = 1; d < 64; d <<= 1) {
+        const int o = __shfl_up(incl, d);
+        if (lane >= d) incl += o;
+      }
+      if (PASS == 1) {
+        int pos = run + incl - pc;
+        while (bits) {
+          const int bit = __ffs(bits) - 1;
+          bits &= bits - 1;
+          bc[pos++] = (i0 + lane) * 32 + bit;
+        }
+      }
+      run += __shfl(incl, 63);
+    }
+    if (PASS == 0 && lane == 0) G->rowgt[R] = (unsigned)run;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();  // the slice is cleared again for the next row
+  }
+}
+
+// One workgroup per head: row pointers of the Interval-Slash heads from the per-row counts above.
+__global__ __launch_bounds__(BT) void idx_diag_scan_kernel(IdxArgs a) {
+  __shared__ unsigned s_scan[BT];
+  const int h = blockIdx.x, tid = threadIdx.x, nb = a.sh.nb;
+  IdxScratch *G = a.scratch + h;
+  if (G->pattern != SA_INTERVAL_SLASH) return;
+  constexpr int RP = kMaxNb / BT;
+  unsigned g[RP], sum = 0;
+#pragma unroll
+  for (int j = 0; j < RP; ++j) {
+    const int R = RP * tid + j;
+    g[j] = R < nb ? G->rowgt[R] : 0u;
+    sum += g[j];
+  }
+  s_scan[tid] = sum;
+  __syncthreads();
+  unsigned run = 0;
+  for (int t = 0; t < tid; ++t) run += s_scan[t];
+  int32_t *rp = a.out.rowptr + (size_t)h * (nb + 1);
+#pragma unroll
+  for (int j = 0; j < RP; ++j) {
+    const int R = RP * tid + j;
+    if (R < nb) rp[R] = (int)run;
+    run += g[j];
+    if (R == nb - 1) rp[nb] = (int)run;
+  }
+}
+
+// The offsets are part of the block CSR now: hand back an empty list.
+__global__ void idx_diag_done_kernel(IdxArgs a) {
+  const int h = blockIdx.x;
+  if ((a.scratch + h)->pattern != SA_INTERVAL_SLASH) return;
+  int32_t *offs = a.out.offs + (size_t)h * a.sh.k_s;
+  for (int i = threadIdx.x; i < a.sh.k_s; i += blockDim.x) offs[i] = -1;
+  if (threadIdx.x == 0) a.out.n_offs[h] = 0;
+}
+
 }  // namespace
 
 size_t index_scratch_bytes(int n_heads) { return sizeof(IdxScratch) * (size_t)n_heads; }
@@ -702,6 +804,12 @@ void launch_finish(const IdxArgs &a, hipStream_t st) {
     if (a.sh.nb <= 256) idx_emit_rows_kernel<4><<<grid, BT, 0, st>>>(a);
     else if (a.sh.nb <= 1024) idx_emit_rows_kernel<16><<<grid, BT, 0, st>>>(a);
     else idx_emit_rows_kernel<kMaxNb / 64><<<grid, BT, 0, st>>>(a);
+  }
+  if (a.sh.diag_blocks) {
+    idx_diag_rows_kernel<0><<<grid, BT, 0, st>>>(a);
+    idx_diag_scan_kernel<<<a.sh.Hq, BT, 0, st>>>(a);
+    idx_diag_rows_kernel<1><<<grid, BT, 0, st>>>(a);
+    idx_diag_done_kernel<<<a.sh.Hq, BT, 0, st>>>(a);
   }
 }
 

@@ -21,6 +21,7 @@ struct Shape {
   int k_v, k_s, k_b, cap_b, sink, local;
   int probe_v, probe_s, lift_num, lift_den;
   int row_select;                 // Block-Cluster heads: 1 = every row keeps its own share of k_b
+  int diag_blocks;                // Interval-Slash heads: 1 = selected diagonals kept as whole blocks
   int nchunks;                    // ceil(N / kChunk)
   int n_cu;                       // compute units of the device the context was created on
   int64_t q_hs, q_rs, kv_hs, kv_rs;

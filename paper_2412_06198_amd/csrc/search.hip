@@ -58,7 +58,8 @@ void candidate_config(const sa_config &parent, int pattern, int64_t x, sa_config
   c->n_q_heads = c->n_kv_heads = 1;
   const int nb = parent.seq_len / parent.block;
   c->local_blocks = 1; c->k_vertical = 1; c->k_slash = 1; c->k_blocks = nb;
-  c->block_select = SA_BLOCKS_GLOBAL;  // the search's Block-Cluster candidate is the one-top-k rule
+  c->block_select = SA_BLOCKS_GLOBAL;  // the search's Block-Cluster candidate is the one-top-k rule,
+  c->diagonal_select = SA_DIAGONALS_EXACT;  // its Interval-Slash candidate the element-exact one
   if (pattern == SA_TRIANGULAR) {
     c->local_blocks = (int32_t)x;
   } else if (pattern == SA_INTERVAL_SLASH) {

@@ -20,7 +20,8 @@ def make_session(Hq, Hkv, N, b, w, bud: orc.Budgets):
     return sa.Session(Hq, Hkv, N, b, w, sink_blocks=bud.sink_blocks, local_blocks=bud.local_blocks,
                       k_vertical=bud.k_vertical, k_slash=bud.k_slash, k_blocks=bud.k_blocks,
                       probe_v=bud.probe_v, probe_s=bud.probe_s, lift_num=bud.lift_num,
-                      lift_den=bud.lift_den, block_select=bud.block_select)
+                      lift_den=bud.lift_den, block_select=bud.block_select,
+                      diagonal_select=bud.diagonal_select)
 
 
 def upload_index(ses, ix: orc.Index):

@@ -147,6 +147,72 @@ def test_per_row_block_topk_brute_force_and_limits():
     assert (a.rowptr == c.rowptr).all() and (a.blkcols[0, :a.rowptr[0, -1]] == c.blkcols[0, :c.rowptr[0, -1]]).all()
 
 
+def _csr_pairs(ix, h, nb):
+    rp = ix.rowptr[h]
+    return {(R, int(C)) for R in range(nb) for C in ix.blkcols[h, rp[R]:rp[R + 1]]}
+
+
+@pytest.mark.parametrize("seed,N,b,ks", [(0, 96, 8, 3), (1, 128, 16, 5), (2, 64, 4, 64)])
+def test_block_widened_diagonals_are_the_smallest_block_cover(seed, N, b, ks):
+    # the kept block pairs are exactly those that hold a (query, key) pair of a selected diagonal,
+    # plus the diagonal blocks: every exact pair is covered, no block is kept without one
+    rng = np.random.default_rng(seed)
+    nb = N // b
+    v = rng.random((2, N)).astype(np.float32)
+    s = rng.random((2, N)).astype(np.float32)
+    blk = np.zeros((2, nb, nb), np.float32)
+    exact = orc.build_index(v, s, blk, N, b, 4, _bud(k_slash=ks, k_blocks=nb), override=[IS, IS])
+    wide = orc.build_index(v, s, blk, N, b, 4, _bud(k_slash=ks, k_blocks=nb, diagonal_select=1),
+                           override=[IS, IS])
+    assert (wide.n_offs == 0).all() and (wide.offs == -1).all()
+    assert (wide.cols == exact.cols).all() and (wide.pattern == exact.pattern).all()
+    i = np.arange(N)
+    for h in range(2):
+        offs = exact.offs[h, :exact.n_offs[h]]
+        want = {(R, R) for R in range(nb)}
+        ii, oo = np.meshgrid(i, offs, indexing="ij")
+        ok = ii >= oo
+        want |= set(zip((ii[ok] // b).tolist(), ((ii[ok] - oo[ok]) // b).tolist()))
+        got = _csr_pairs(wide, h, nb)
+        assert got == want
+        rp = wide.rowptr[h]
+        for R in range(nb):
+            row = wide.blkcols[h, rp[R]:rp[R + 1]]
+            assert (np.diff(row) > 0).all() and row[-1] == R
+        assert (wide.blkcols[h, rp[nb]:] == -1).all()
+
+
+def test_block_widened_diagonals_special_cases():
+    rng = np.random.default_rng(9)
+    N, w = 48, 4
+    Q, K, V = gen.random_qkv(1, 1, N, 128, seed=48)
+    v = rng.random((1, N)).astype(np.float32)
+    s = rng.random((1, N)).astype(np.float32)
+    # block size 1: a block pair is an element pair, the two forms give the same attention output
+    blk = np.zeros((1, N, N), np.float32)
+    a = orc.build_index(v, s, blk, N, 1, w, _bud(k_slash=5, k_blocks=N), override=[IS])
+    c = orc.build_index(v, s, blk, N, 1, w, _bud(k_slash=5, k_blocks=N, diagonal_select=1), override=[IS])
+    Oa, _, ka = orc.masked_rows(Q, K, V, 1, a)
+    Oc, _, kc = orc.masked_rows(Q, K, V, 1, c)
+    assert (ka == kc).all() and np.abs(Oa - Oc).max() < 1e-12
+    # only offset 0 selected: nothing beyond the diagonal blocks
+    s0 = np.zeros((1, N), np.float32); s0[0, 0] = 1.0
+    blk = np.zeros((1, 6, 6), np.float32)
+    c = orc.build_index(v, s0, blk, N, 8, w, _bud(k_slash=1, k_blocks=6, diagonal_select=1), override=[IS])
+    assert _csr_pairs(c, 0, 6) == {(R, R) for R in range(6)}
+    # offset b: exactly the block below the diagonal; offset b + 1: the two blocks below it
+    for o, want_extra in ((8, {(R, R - 1) for R in range(1, 6)}),
+                          (9, {(R, R - 1) for R in range(1, 6)} | {(R, R - 2) for R in range(2, 6)})):
+        so = np.zeros((1, N), np.float32); so[0, o] = 1.0
+        c = orc.build_index(v, so, blk, N, 8, w, _bud(k_slash=1, k_blocks=6, diagonal_select=1), override=[IS])
+        assert _csr_pairs(c, 0, 6) == {(R, R) for R in range(6)} | want_extra
+    # the other patterns ignore the setting
+    for pat in (T, BC):
+        a = orc.build_index(v, s, blk, N, 8, w, _bud(k_blocks=9), override=[pat])
+        c = orc.build_index(v, s, blk, N, 8, w, _bud(k_blocks=9, diagonal_select=1), override=[pat])
+        assert all(x.tobytes() == y.tobytes() for x, y in zip(a.arrays()[:6], c.arrays()[:6]))
+
+
 def test_k_larger_than_candidates_is_clamped():
     N, b = 16, 4
     v = np.arange(16, dtype=np.float32)[None]
