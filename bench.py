@@ -54,7 +54,7 @@ def cpu_baseline(orc, data, wl, bud, sample_rows):
 
 
 def run_workload(name, steps, warmup, layers, with_cpu, sample_rows, with_dense=False, block_select=0,
-                 diagonal_select=0):
+                 diagonal_select=0, prewarm_s=PREWARM_S):
     import numpy as np
     import torch
 
@@ -93,7 +93,7 @@ def run_workload(name, steps, warmup, layers, with_cpu, sample_rows, with_dense=
     # the device leaves its idle clocks only after some tens of milliseconds of load: bring it to
     # the steady state first (untimed, like the W warm-up steps that follow)
     t_pre, n_pre = time.perf_counter(), 0
-    while time.perf_counter() - t_pre < PREWARM_S:
+    while time.perf_counter() - t_pre < prewarm_s:
         step(n_pre)
         n_pre += 1
         if n_pre % 8 == 0:
@@ -431,6 +431,8 @@ def main():
     ap.add_argument("--layers", type=int, default=2, help="distinct seeded layers kept resident (cfg5 sweep: 32)")
     ap.add_argument("--also", default="cfg3", help="second workload reported under 'also' ('' to skip)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--prewarm", type=float, default=PREWARM_S,
+                    help="seconds of untimed load before the warm-up steps (0 for counter-collection runs)")
     ap.add_argument("--sample-rows", type=int, default=16384,
                     help="rows per head of the oracle's masked attention in the cpu_baseline leg (about 10 s at 128K)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -483,11 +485,11 @@ def main():
     bsel = 1 if a.block_select == "row" else 0
     dsel = 1 if a.diagonals == "blocks" else 0
     main_res = run_workload(a.workload, a.steps, a.warmup, a.layers, not a.no_cpu_baseline, a.sample_rows,
-                            block_select=bsel, diagonal_select=dsel)
+                            block_select=bsel, diagonal_select=dsel, prewarm_s=a.prewarm)
     also = None
     if a.also and a.also != a.workload:
         also = run_workload(a.also, max(a.steps, 20), a.warmup, min(a.layers, 2), False, a.sample_rows,
-                            with_dense=True, block_select=bsel, diagonal_select=dsel)
+                            with_dense=True, block_select=bsel, diagonal_select=dsel, prewarm_s=a.prewarm)
 
     traffic = None
     tp = os.path.join(ROOT, "profiles", f"traffic_{a.workload}.json")
