@@ -133,6 +133,26 @@ def run_workload(name, steps, warmup, layers, with_cpu, sample_rows, with_dense=
     ph1 = np.array([[e[k].elapsed_time(e[k + 1]) for k in range(2)] for e in evs1]).mean(0)
     log(f"[{name}] one-call form: ms/step wall {wall1_ms / steps:.3f}; estimate+index {ph1[0]:.3f} attention {ph1[1]:.3f}")
 
+    # the three-call step recorded once per resident layer into a HIP graph and replayed
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graphs = []
+    for l in range(layers):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            step(l)
+        graphs.append(g)
+    for i in range(warmup):
+        graphs[i % layers].replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        graphs[i % layers].replay()
+    torch.cuda.synchronize()
+    wallg_ms = (time.perf_counter() - t0) * 1e3
+    log(f"[{name}] graph replay of the three calls: ms/step wall {wallg_ms / steps:.3f}")
+    del graphs
+
     # work accounting (untimed): tiles multiplied and kept pairs per layer, pattern choices
     tiles, kept, confusion = [], [], np.zeros((3, 3), int)
     for l in range(layers):
@@ -153,6 +173,7 @@ def run_workload(name, steps, warmup, layers, with_cpu, sample_rows, with_dense=
         "workload": name, "ms_per_step": wall_ms / steps, "prewarm_steps_untimed": n_pre,
         "one_call_estimate_and_index": {"ms_per_step": wall1_ms / steps, "estimate_and_index": float(ph1[0]),
                                         "attention": float(ph1[1])},
+        "graph_replay_ms_per_step": wallg_ms / steps,
         "phases_ms": {"estimate": float(t_est), "index": float(t_idx), "attention": float(t_attn),
                       "attention_p95": float(np.percentile(ph[:, 2], 95))},
         "tflops": {"kept": f_mask / t_attn / 1e9, "tiles": f_tiles / t_attn / 1e9,
@@ -307,12 +328,31 @@ def run_sweep(steps):
             e1.record()
             torch.cuda.synchronize()
             res[kind] = e0.elapsed_time(e1) / n
+            if kind == "sparse":
+                # the same step recorded once into a HIP graph and replayed: what the ten small
+                # launches of the index builder cost on the host side at short sequences
+                side = torch.cuda.Stream()
+                side.wait_stream(torch.cuda.current_stream())
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph, stream=side):
+                    step()
+                for _ in range(2):
+                    graph.replay()
+                torch.cuda.synchronize()
+                e0.record()
+                for _ in range(n):
+                    graph.replay()
+                e1.record()
+                torch.cuda.synchronize()
+                res["sparse_graph"] = e0.elapsed_time(e1) / n
+                del graph
             ses.close()
         f_dense = 4.0 * d * Hq * N * (N + 1) / 2.0
         rows.append({"seq_len": N, "block": b, "keep": keep, "sparse_ms": round(res["sparse"], 4),
+                     "sparse_graph_replay_ms": round(res["sparse_graph"], 4),
                      "dense_ms": round(res["dense"], 4), "speedup": round(res["dense"] / res["sparse"], 3),
                      "dense_TFLOPs": round(f_dense / res["dense"] / 1e9, 1)})
-        log(f"[sweep] N={N}: sparse {res['sparse']:.3f} ms, dense {res['dense']:.3f} ms "
+        log(f"[sweep] N={N}: sparse {res['sparse']:.3f} ms (graph replay {res['sparse_graph']:.3f}), dense {res['dense']:.3f} ms "
             f"({rows[-1]['dense_TFLOPs']} TFLOP/s), ratio {rows[-1]['speedup']}")
         del Q, K, V, O
         torch.cuda.empty_cache()
