@@ -234,6 +234,24 @@ __device__ inline void wave_find_kth(const unsigned *hist, int nbins, unsigned k
   rank = __shfl(r, owner);
 }
 
+// Exclusive prefixes of two values per thread over the BT threads of a workgroup: shuffles inside
+// the waves, the wave totals through LDS (wsum: 2 * WPB words).  Called by all threads.
+__device__ inline void block_exclusive_scan2(unsigned &a, unsigned &b, unsigned *wsum) {
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  unsigned ia = a, ib = b;
+  for (int d = 1; d < 64; d <<= 1) {
+    const unsigned oa = __shfl_up(ia, d), ob = __shfl_up(ib, d);
+    if (lane >= d) { ia += oa; ib += ob; }
+  }
+  if (lane == 63) { wsum[wv] = ia; wsum[WPB + wv] = ib; }
+  __syncthreads();
+  unsigned ba = 0, bb = 0;
+  for (int w = 0; w < wv; ++w) { ba += wsum[w]; bb += wsum[WPB + w]; }
+  __syncthreads();
+  a = ba + ia - a;
+  b = bb + ib - b;
+}
+
 __global__ void idx_zero_kernel(IdxScratch *scratch) {
   unsigned *p = (unsigned *)(scratch + blockIdx.x);
   for (size_t i = threadIdx.x; i < kZeroWords; i += blockDim.x) p[i] = 0u;
@@ -458,8 +476,7 @@ __device__ inline int decide_pattern(const IdxArgs &a, const IdxScratch *G, int 
 
 // One workgroup per head: pattern decision, prefixes of the per-part and per-row counts, rowptr.
 __global__ __launch_bounds__(BT) void idx_scan_kernel(IdxArgs a) {
-  __shared__ unsigned s_scan[BT];
-  __shared__ unsigned s_scan2[BT];
+  __shared__ unsigned s_wsum[2 * WPB];
   __shared__ int s_pat;
   const Shape &sh = a.sh;
   const int h = blockIdx.x, tid = threadIdx.x;
@@ -477,20 +494,14 @@ __global__ __launch_bounds__(BT) void idx_scan_kernel(IdxArgs a) {
   }
   // ---- exclusive prefixes of the wave-part counts of v and s (PW <= 256 = one per thread) --------
   for (int arr = 0; arr < 2; ++arr) {
-    __syncthreads();
-    s_scan[tid] = tid < a.PW ? G->wgt[arr][tid] : 0u;
-    s_scan2[tid] = tid < a.PW ? G->weq[arr][tid] : 0u;
-    __syncthreads();
-    unsigned pg = 0, pe = 0;
-    for (int t = 0; t < tid; ++t) { pg += s_scan[t]; pe += s_scan2[t]; }
+    unsigned pg = tid < a.PW ? G->wgt[arr][tid] : 0u, pe = tid < a.PW ? G->weq[arr][tid] : 0u;
+    block_exclusive_scan2(pg, pe, s_wsum);
     if (tid < a.PW) { G->wgt[arr][tid] = pg; G->weq[arr][tid] = pe; }
   }
-  __syncthreads();
-  const int pat = s_pat;
+  const int pat = s_pat;  // written before the barriers of the scans above
   const bool bc_global = pat == SA_BLOCK_CLUSTER && !sh.row_select;
   // ---- row prefixes: thread t owns RP consecutive rows (nb <= kMaxNb) ------------------------------
   constexpr int RP = kMaxNb / BT;
-  __syncthreads();
   unsigned g16[RP], e16[RP], gs = 0, es = 0;
 #pragma unroll
   for (int j = 0; j < RP; ++j) {
@@ -512,11 +523,8 @@ __global__ __launch_bounds__(BT) void idx_scan_kernel(IdxArgs a) {
     g16[j] = g; e16[j] = e;
     gs += g; es += e;
   }
-  s_scan[tid] = gs;
-  s_scan2[tid] = es;
-  __syncthreads();
-  unsigned eg = 0, ee = 0;
-  for (int t = 0; t < tid; ++t) { eg += s_scan[t]; ee += s_scan2[t]; }
+  unsigned eg = gs, ee = es;
+  block_exclusive_scan2(eg, ee, s_wsum);
   int32_t *rp = a.out.rowptr + (size_t)h * (nb + 1);
 #pragma unroll
   for (int j = 0; j < RP; ++j) {
@@ -721,7 +729,7 @@ __global__ __launch_bounds__(BT) void idx_diag_rows_kernel(IdxArgs a) {
 
 // One workgroup per head: row pointers of the Interval-Slash heads from the per-row counts above.
 __global__ __launch_bounds__(BT) void idx_diag_scan_kernel(IdxArgs a) {
-  __shared__ unsigned s_scan[BT];
+  __shared__ unsigned s_wsum[2 * WPB];
   const int h = blockIdx.x, tid = threadIdx.x, nb = a.sh.nb;
   IdxScratch *G = a.scratch + h;
   if (G->pattern != SA_INTERVAL_SLASH) return;
@@ -733,10 +741,8 @@ __global__ __launch_bounds__(BT) void idx_diag_scan_kernel(IdxArgs a) {
     g[j] = R < nb ? G->rowgt[R] : 0u;
     sum += g[j];
   }
-  s_scan[tid] = sum;
-  __syncthreads();
-  unsigned run = 0;
-  for (int t = 0; t < tid; ++t) run += s_scan[t];
+  unsigned run = sum, unused = 0;
+  block_exclusive_scan2(run, unused, s_wsum);
   int32_t *rp = a.out.rowptr + (size_t)h * (nb + 1);
 #pragma unroll
   for (int j = 0; j < RP; ++j) {
