@@ -43,7 +43,7 @@ __device__ inline void store_split(float *means_row, int d, float x) {
 // a thread are in flight before the first sum.  The kernel is pure HBM streaming and runs beside
 // the window passes (vector ALU bound): it is launched with kQMeanLdsPad bytes of unused dynamic
 // LDS so that it never holds more than a few wave slots of a compute unit.
-constexpr int kQMeanLdsPad = 40 * 1024;
+constexpr int kQMeanLdsPad = 24 * 1024;
 
 template <int RPT>
 __global__ __launch_bounds__(256) void q_block_mean_kernel(const uint16_t *__restrict__ Q, Shape sh,
