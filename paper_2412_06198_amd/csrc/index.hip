@@ -9,7 +9,7 @@
 // Five selections run side by side for every head, so that nothing waits on the
 // pattern decision: the probe_v / probe_s best of v and s (pattern rule), the
 // k_v best columns, the k_s best diagonals, the k_b - nb best blocks.  Each is a
-// radix select in three levels (11 + 11 + 10 key bits).  Every level is a
+// radix select in three levels (11 + 10 + 10 key bits; the sign bit is clear).  Every level is a
 // launch of P workgroups per head (LDS histograms, flushed to global memory with
 // integer atomics) followed by a one-workgroup-per-head launch that reads the
 // merged histogram and fixes the next digit: kernel boundaries are the only
@@ -38,7 +38,7 @@ constexpr int kMaxParts = 64;      // workgroups per head
 constexpr int kMaxPW = kMaxParts * WPB;
 constexpr int kMaxNb = kMaxSeq / 64;
 constexpr int NSEL = 5;            // 0: v probe, 1: s probe, 2: v top k_v, 3: s top k_s, 4: blk top k_b - nb
-constexpr int L1BINS = 2048, L2BINS = 2048, L3BINS = 1024;  // 11 + 11 + 10 key bits
+constexpr int L1BINS = 2048, L2BINS = 1024, L3BINS = 1024;  // 11 + 10 + 10 key bits below the sign bit
 
 // per-head scratch in the workspace
 struct IdxScratch {
@@ -258,13 +258,13 @@ __global__ void idx_zero_kernel(IdxScratch *scratch) {
 }
 
 // ---- level histograms ------------------------------------------------------------------------------
-// LEVEL 1: bits 31..21 of every key, one histogram per array.
-// LEVEL 2: bits 20..10 of the keys whose bits 31..21 equal the selection's prefix.
+// LEVEL 1: bits 30..20 of every key (scores are >= +0: bit 31 is clear), one histogram per array.
+// LEVEL 2: bits 19..10 of the keys whose bits 30..20 equal the selection's prefix.
 // LEVEL 3: bits  9..0 of the keys whose bits 31..10 equal the selection's prefix.
 template <int LEVEL>
 __global__ __launch_bounds__(BT) void idx_hist_kernel(IdxArgs a) {
   constexpr int NH = LEVEL == 1 ? 3 : NSEL;
-  constexpr int BINS = LEVEL == 3 ? L3BINS : L1BINS;
+  constexpr int BINS = LEVEL == 1 ? L1BINS : L2BINS;
   __shared__ __attribute__((aligned(16))) unsigned hist[NH][BINS];
   __shared__ unsigned long long red64[2][WPB];
   const Shape &sh = a.sh;
@@ -299,10 +299,10 @@ __global__ __launch_bounds__(BT) void idx_hist_kernel(IdxArgs a) {
       const bool ok = i0 + j < lim;
       const unsigned key = v.k[j];
       if (LEVEL == 1) {
-        hist_add(hist[arr], key >> 21, ok);
+        hist_add(hist[arr], min(key >> 20, (unsigned)L1BINS - 1u), ok);  // the sign bit of a score is 0
       } else {
-        const unsigned hi_bits = LEVEL == 2 ? key >> 21 : key >> 10;
-        const unsigned bin = LEVEL == 2 ? (key >> 10) & 2047u : key & 1023u;
+        const unsigned hi_bits = LEVEL == 2 ? key >> 20 : key >> 10;
+        const unsigned bin = LEVEL == 2 ? (key >> 10) & 1023u : key & 1023u;
         if (arr == 2) {
           hist_add(hist[NH - 1], bin, ok && act[4] && hi_bits == pre[4]);
         } else {
@@ -350,7 +350,7 @@ __global__ __launch_bounds__(BT) void idx_hist_kernel(IdxArgs a) {
 template <int LEVEL>
 __global__ __launch_bounds__(BT) void idx_select_kernel(IdxArgs a) {
   constexpr int NH = LEVEL == 1 ? 3 : NSEL;
-  constexpr int BINS = LEVEL == 3 ? L3BINS : L1BINS;
+  constexpr int BINS = LEVEL == 1 ? L1BINS : L2BINS;
   __shared__ __attribute__((aligned(16))) unsigned hist[NH][BINS];
   const int h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   IdxScratch *G = a.scratch + h;
@@ -374,7 +374,7 @@ __global__ __launch_bounds__(BT) void idx_select_kernel(IdxArgs a) {
         G->prefix[q] = bin;
         G->remaining[q] = rank;
       } else if (LEVEL == 2) {
-        G->prefix[q] = (pre << 11) | bin;
+        G->prefix[q] = (pre << 10) | bin;
         G->remaining[q] = rank;
       } else {
         G->thr[q] = (pre << 10) | bin;
