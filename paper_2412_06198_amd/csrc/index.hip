@@ -265,8 +265,8 @@ template <int LEVEL>
 __global__ __launch_bounds__(BT) void idx_hist_kernel(IdxArgs a) {
   constexpr int NH = LEVEL == 1 ? 3 : NSEL;
   constexpr int BINS = LEVEL == 1 ? L1BINS : L2BINS;
+  // levels 2 and 3: 20 KB, nothing else in LDS, so that eight workgroups (every wave slot) fit a CU
   __shared__ __attribute__((aligned(16))) unsigned hist[NH][BINS];
-  __shared__ unsigned long long red64[2][WPB];
   const Shape &sh = a.sh;
   const int p = blockIdx.x, h = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int N = sh.N, nb = sh.nb;
@@ -328,21 +328,25 @@ __global__ __launch_bounds__(BT) void idx_hist_kernel(IdxArgs a) {
   if (do_blk)
     wave_rows_visit4(bb, nb, gw, a.PW, (nb & 3) == 0, [](int) {},
                      [&](const Keys4 &v, int i0, int lim) { visit(v, i0, lim, 2); }, [](int) {});
-  if (LEVEL == 1) {
-    for (int d = 32; d >= 1; d >>= 1) { vt += __shfl_xor(vt, d); ct += __shfl_xor(ct, d); }
-    if (lane == 0) { red64[0][wv] = vt; red64[1][wv] = ct; }
-  }
   __syncthreads();
   unsigned *gh = LEVEL == 1 ? &G->hist1[0][0] : (LEVEL == 2 ? &G->hist2[0][0] : &G->hist3[0][0]);
   for (int i = tid; i < NH * BINS; i += BT) {
     const unsigned c = (&hist[0][0])[i];
     if (c) atomicAdd(&gh[i], c);
   }
-  if (LEVEL == 1 && do_vs && tid == 0) {
-    unsigned long long tv = 0, tc = 0;
-    for (int w = 0; w < WPB; ++w) { tv += red64[0][w]; tc += red64[1][w]; }
-    atomicAdd(&G->vtot, tv);
-    atomicAdd(&G->ct, tc);
+  if (LEVEL == 1 && do_vs) {
+    // the two 64-bit sums of the workgroup, through the histogram's LDS once it is flushed
+    for (int d = 32; d >= 1; d >>= 1) { vt += __shfl_xor(vt, d); ct += __shfl_xor(ct, d); }
+    unsigned long long *red64 = (unsigned long long *)&hist[0][0];
+    __syncthreads();
+    if (lane == 0) { red64[wv] = vt; red64[WPB + wv] = ct; }
+    __syncthreads();
+    if (tid == 0) {
+      unsigned long long tv = 0, tc = 0;
+      for (int w = 0; w < WPB; ++w) { tv += red64[w]; tc += red64[WPB + w]; }
+      atomicAdd(&G->vtot, tv);
+      atomicAdd(&G->ct, tc);
+    }
   }
 }
 
@@ -773,9 +777,13 @@ IdxArgs index_args(const Shape &sh, const Workspace &ws, sa_scores in, const Ove
   a.v = (const unsigned *)in.v; a.s = (const unsigned *)in.s; a.blk = (const unsigned *)in.blk;
   a.scratch = (IdxScratch *)ws.idx;
   a.sh = sh; a.ov = ov; a.out = out;
-  int P = sh.N / 2048;
+  // Workgroups per head.  Every launch is a chain of dependent memory round trips per wave, so more,
+  // shorter waves win until the per-workgroup costs (clearing and flushing the LDS histograms) take
+  // over: measured best at 32 per head up to 64K tokens and 64 at 128K, 256 keys per wave at least.
+  int P = sh.N / 256;
+  const int pmax = sh.N <= 65536 ? 32 : kMaxParts;
   if (P < 1) P = 1;
-  if (P > kMaxParts) P = kMaxParts;
+  if (P > pmax) P = pmax;
   a.P = P; a.PW = P * WPB;
   a.seg = ((sh.N + a.PW - 1) / a.PW + 255) / 256 * 256;
   const long long ncand = (long long)sh.nb * (sh.nb - 1) / 2;
