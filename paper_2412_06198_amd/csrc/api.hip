@@ -120,7 +120,10 @@ sa_status sa_create(const sa_config *cfg, sa_ctx **out) {
   }
   if (cap > 0x7FFFFFFFll) { delete c; return SA_ERR_UNSUPPORTED; }
   s.cap_b = (int)cap;
-  s.nchunks = (s.N + sa::kChunk - 1) / sa::kChunk;
+  // keys per workgroup of the window passes: 1024 measured 3 % faster than 512 at 128K, equal at
+  // 32K-64K; short sequences keep 512 for the sake of parallelism
+  s.chunk = s.N >= 32768 ? 1024 : 512;
+  s.nchunks = (s.N + s.chunk - 1) / s.chunk;
   s.q_rs = cfg->q_row_stride ? cfg->q_row_stride : sa::kHeadDim;
   s.q_hs = cfg->q_head_stride ? cfg->q_head_stride : (int64_t)s.N * s.q_rs;
   s.kv_rs = cfg->kv_row_stride ? cfg->kv_row_stride : sa::kHeadDim;

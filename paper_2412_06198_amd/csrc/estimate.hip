@@ -145,8 +145,8 @@ __global__ __launch_bounds__(256) void window_stats_kernel(const uint16_t *__res
   const int hsub = 4 * blockIdx.z + wv;
   const bool head_ok = hsub < sh.g;
   const int hq = kvh * sh.g + (head_ok ? hsub : 0);
-  const int jc0 = chunk * kChunk;
-  const int jc1 = min(jc0 + kChunk, sh.N);
+  const int jc0 = chunk * sh.chunk;
+  const int jc1 = min(jc0 + sh.chunk, sh.N);
   const int nt = (jc1 - jc0) >> 6;  // N is a multiple of 64: whole tiles only
   const uint16_t *Kh = K + (size_t)kvh * sh.kv_hs + (size_t)jc0 * sh.kv_rs;
   const bool do_means = blockIdx.z == 0;
@@ -376,8 +376,8 @@ __global__ __launch_bounds__(256) void window_scores_kernel(const uint16_t *__re
   const int hsub = 4 * blockIdx.z + wv;
   const bool head_ok = hsub < sh.g;
   const int hq = kvh * sh.g + (head_ok ? hsub : 0);
-  const int jc0 = chunk * kChunk;
-  const int jc1 = min(jc0 + kChunk, sh.N);
+  const int jc0 = chunk * sh.chunk;
+  const int jc1 = min(jc0 + sh.chunk, sh.N);
   const int nt = (jc1 - jc0) >> 6;
   const uint16_t *Kh = K + (size_t)kvh * sh.kv_hs + (size_t)jc0 * sh.kv_rs;
 

@@ -10,7 +10,6 @@ namespace sa {
 constexpr int kHeadDim = 128;
 constexpr int kMaxHeads = 128;
 constexpr int kWin = 64;          // rows of the last-query window the estimator tiles for
-constexpr int kChunk = 512;       // keys per estimator workgroup (window passes)
 constexpr int kMaxSeq = 262144;   // key-tile bitmaps of the attention kernel cover this many keys
 
 struct Override { int8_t pat[kMaxHeads]; };
@@ -22,7 +21,7 @@ struct Shape {
   int probe_v, probe_s, lift_num, lift_den;
   int row_select;                 // Block-Cluster heads: 1 = every row keeps its own share of k_b
   int diag_blocks;                // Interval-Slash heads: 1 = selected diagonals kept as whole blocks
-  int nchunks;                    // ceil(N / kChunk)
+  int chunk, nchunks;             // keys per estimator workgroup (window passes), ceil(N / chunk)
   int n_cu;                       // compute units of the device the context was created on
   int64_t q_hs, q_rs, kv_hs, kv_rs;
   float scale;
