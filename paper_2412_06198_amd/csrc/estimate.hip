@@ -54,7 +54,13 @@ __global__ __launch_bounds__(256) void q_block_mean_kernel(const uint16_t *__res
   const int cc = tid & 15, rg = tid >> 4;
   uint4 x[RPT];
 #pragma unroll
-  for (int n = 0; n < RPT; ++n) x[n] = *(const uint4 *)(src + (size_t)(rg + 16 * n) * sh.q_rs + cc * 8);
+  for (int n = 0; n < RPT; ++n) {
+    // read once: a streaming (non-temporal) load leaves the caches to K, which the second window
+    // pass reads again
+    typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+    const u32x4_t v = __builtin_nontemporal_load((const u32x4_t *)(src + (size_t)(rg + 16 * n) * sh.q_rs + cc * 8));
+    x[n] = make_uint4(v.x, v.y, v.z, v.w);
+  }
   float acc[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) acc[e] = 0.f;
