@@ -28,8 +28,9 @@ sa_status fail(sa_ctx *c, sa_status st, const char *msg) {
 void carve(sa_ctx *c) {
   const sa::Shape &s = c->sh;
   size_t o = 0;
-  c->off[0] = o; o += align256((size_t)s.Hq * s.nb * sa::kHeadDim * 4);
-  c->off[1] = o; o += align256((size_t)s.Hkv * s.nb * sa::kHeadDim * 4);
+  const size_t nb16 = (size_t)(s.nb + 15) / 16 * 16;  // block means are stored in tiles of 16 rows
+  c->off[0] = o; o += align256((size_t)s.Hq * nb16 * sa::kHeadDim * 4);
+  c->off[1] = o; o += align256((size_t)s.Hkv * nb16 * sa::kHeadDim * 4);
   c->off[2] = o; o += align256((size_t)s.Hq * s.nchunks * sa::kWin * 8);
   c->off[3] = o; o += align256((size_t)s.Hq * sa::kWin * 8);
   c->off[4] = o; o += align256((size_t)s.Hq * (s.N / 32) * 4);

@@ -28,14 +28,22 @@ __device__ inline float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b 
 
 // Block means are kept as two bf16 numbers, head + remainder (x = hi + lo to about 2^-17 |x|), so
 // that the block map can form their products on the bf16 matrix pipe: hi.hi + hi.lo + lo.hi with
-// fp32 accumulation differs from the fp32 product by about 2^-16 of it.  Row r of a means array
-// holds 128 heads followed by 128 remainders (512 bytes, the size of the fp32 row it replaces).
-__device__ inline void store_split(float *means_row, int d, float x) {
+// fp32 accumulation differs from the fp32 product by about 2^-16 of it.
+// A means array is laid out in the order in which the block map's matrix instruction wants its
+// operands: per head ceil(nb/16) tiles of 16 rows, 8 KB each = [part: heads, remainders][k-step
+// st = d/32][g = d%32/8][row n = R%16][8 elements], so that lane n + 16 g of a wave reads 16
+// contiguous bytes of a contiguous 1 KB per instruction.  (With plain rows every quarter-wave
+// touched 16 different cache lines, and the block map spent half its time in the L1's tag
+// lookups.)  Rows past nb in the last tile are never written; nothing that is kept depends on them.
+__device__ inline size_t means_tiles(int nb) { return (size_t)((nb + 15) / 16); }
+
+__device__ inline void store_split(float *means_head, int R, int d, float x) {
   const __bf16 hi = (__bf16)x;
   const __bf16 lo = (__bf16)(x - (float)hi);
-  uint16_t *row = (uint16_t *)means_row;
-  row[d] = __builtin_bit_cast(uint16_t, hi);
-  row[kHeadDim + d] = __builtin_bit_cast(uint16_t, lo);
+  uint16_t *tile = (uint16_t *)means_head + (size_t)(R >> 4) * 4096;
+  const int o = (d >> 5) * 512 + ((d >> 3) & 3) * 128 + (R & 15) * 8 + (d & 7);
+  tile[o] = __builtin_bit_cast(uint16_t, hi);
+  tile[2048 + o] = __builtin_bit_cast(uint16_t, lo);
 }
 
 // ------------------------------------------------------------------ Q block means
@@ -80,7 +88,7 @@ __global__ __launch_bounds__(256) void q_block_mean_kernel(const uint16_t *__res
     float sum = 0.f;
 #pragma unroll
     for (int r = 0; r < 16; ++r) sum += red[r][tid];
-    store_split(qblk + ((size_t)h * sh.nb + R) * kHeadDim, tid, sum * (1.0f / (float)sh.b));
+    store_split(qblk + (size_t)h * means_tiles(sh.nb) * 2048, R, tid, sum * (1.0f / (float)sh.b));
   }
 }
 
@@ -187,7 +195,7 @@ __global__ __launch_bounds__(256) void window_stats_kernel(const uint16_t *__res
     if (do_means) {
       if (pending >= 0 && tid < kHeadDim) {
         const float(*ps)[kHeadDim] = ksum[pending & 1];
-        store_split(kblk + ((size_t)kvh * sh.nb + pending) * kHeadDim, tid,
+        store_split(kblk + (size_t)kvh * means_tiles(sh.nb) * 2048, pending, tid,
                     ((ps[0][tid] + ps[1][tid]) + (ps[2][tid] + ps[3][tid])) * (1.0f / (float)sh.b));
       }
       pending = -1;
@@ -261,7 +269,7 @@ __global__ __launch_bounds__(256) void window_stats_kernel(const uint16_t *__res
     __syncthreads();
     if (pending >= 0 && tid < kHeadDim) {
       const float(*ps)[kHeadDim] = ksum[pending & 1];
-      store_split(kblk + ((size_t)kvh * sh.nb + pending) * kHeadDim, tid,
+      store_split(kblk + (size_t)kvh * means_tiles(sh.nb) * 2048, pending, tid,
                   ((ps[0][tid] + ps[1][tid]) + (ps[2][tid] + ps[3][tid])) * (1.0f / (float)sh.b));
     }
   }
@@ -491,40 +499,34 @@ __global__ __launch_bounds__(64 * kMapWaves, (MT <= 8 ? 4 : 2)) void block_map_k
   }
   const int R0 = 16 * strip;
   const int T = strip + 1;  // column tiles 0..strip hold every C <= R of this strip
-  const float *qsrc = qblk + (size_t)h * nb * kHeadDim;
-  const float *ksrc = kblk + (size_t)(h / sh.g) * nb * kHeadDim;
+  // tile t of a means array: 8 KB = [part][st][lane][16 bytes]
+  const uint16_t *qsrc = (const uint16_t *)(qblk + (size_t)h * means_tiles(nb) * 2048) + 8 * lane;
+  const uint16_t *ksrc = (const uint16_t *)(kblk + (size_t)(h / sh.g) * means_tiles(nb) * 2048) + 8 * lane;
 
   // operands of v_mfma_f32_16x16x32_bf16: lane (n = row of A / column of B, g) holds elements
-  // 32 st + 8 g .. + 7 of its mean, st = 0..3: 16 bytes of heads and 16 bytes of remainders per step
+  // 32 st + 8 g .. + 7 of its mean, st = 0..3: 16 bytes of heads and 16 bytes of remainders per step,
+  // which is the order the means are stored in
   bf16x8 ah[4], al[4];
   {
-    const uint16_t *ap = (const uint16_t *)(qsrc + (size_t)min(R0 + n, nb - 1) * kHeadDim) + 8 * g;
+    const uint16_t *ap = qsrc + (size_t)strip * 4096;
 #pragma unroll
     for (int st = 0; st < 4; ++st) {
-      ah[st] = *(const bf16x8 *)(ap + 32 * st);
-      al[st] = *(const bf16x8 *)(ap + kHeadDim + 32 * st);
+      ah[st] = *(const bf16x8 *)(ap + 512 * st);
+      al[st] = *(const bf16x8 *)(ap + 2048 + 512 * st);
     }
   }
   f32x4 acc[MT];
   bf16x8 bh[4], bl[4];
-  if (wv < T) {
-    const uint16_t *bp = (const uint16_t *)(ksrc + (size_t)min(16 * wv + n, nb - 1) * kHeadDim) + 8 * g;
-#pragma unroll
-    for (int st = 0; st < 4; ++st) {
-      bh[st] = *(const bf16x8 *)(bp + 32 * st);
-      bl[st] = *(const bf16x8 *)(bp + kHeadDim + 32 * st);
-    }
-  }
 #pragma unroll
   for (int k = 0; k < MT; ++k) {
     const int tc = kMapWaves * k + wv;
     if (tc < T) {
       {
-        const uint16_t *bp = (const uint16_t *)(ksrc + (size_t)min(16 * tc + n, nb - 1) * kHeadDim) + 8 * g;
+        const uint16_t *bp = ksrc + (size_t)tc * 4096;
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
-          bh[st] = *(const bf16x8 *)(bp + 32 * st);
-          bl[st] = *(const bf16x8 *)(bp + kHeadDim + 32 * st);
+          bh[st] = *(const bf16x8 *)(bp + 512 * st);
+          bl[st] = *(const bf16x8 *)(bp + 2048 + 512 * st);
         }
       }
       // three independent chains: heads x heads, and the two cross terms (remainder x remainder,

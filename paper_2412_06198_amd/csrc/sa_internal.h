@@ -28,7 +28,7 @@ struct Shape {
 };
 
 struct Workspace {
-  float *qblk, *kblk;             // [Hq][nb][128], [Hkv][nb][128] block means
+  float *qblk, *kblk;             // [Hq][ceil(nb/16)] and [Hkv][ceil(nb/16)] tiles (8 KB) of block means
   float2 *part;                   // [Hq][nchunks][64] partial (max, sum) of the window rows
   float2 *stats;                  // [Hq][64] (max * scale*log2e, 1/sum)
   uint32_t *colbits;              // [Hq][N/32] membership bitmap of the selected columns
