@@ -531,13 +531,13 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
 
   // ---- selected diagonals: one 32-key tile per (wave, offset), no workgroup barriers -----------
   // For offset o the 32 queries of this wave need the 32 keys r0-o .. r0-o+31, and in
-  // S^T = K Q^T (32 keys x 32 queries) the wanted entries are the main diagonal.  K goes from
-  // global memory straight into the A operand; V is copied by the LDS DMA into a wave-private
-  // tile for the transposing read.  An entry is dropped when its key block is kept by the CSR
-  // or its key is a selected column: those tiles already counted it.
-  // Nothing here is reused, so the phase lives on memory latency: the reads of the next offset
-  // (column-bitmap words, K, V - in that order) are issued as soon as S^T has consumed the K
-  // registers, and each wave has two V tiles.
+  // S^T = K Q^T (32 keys x 32 queries) the wanted entries are the main diagonal.  K and V are
+  // copied by the LDS DMA into a wave-private K tile and V tile (8 KB each, swizzled like the
+  // shared tiles) and read from there like any tile.  An entry is dropped when its key block is
+  // kept by the CSR or its key is a selected column: those tiles already counted it.
+  // Nothing here is reused, so the phase lives on the memory path: the next offset's K is
+  // requested as soon as S^T has read this offset's K tile, its V as soon as the PV product has
+  // read this offset's V tile, so each copy has half an offset to land.
   __builtin_amdgcn_s_setprio(0);
   if (tid == 0 && home_open) {  // used at the next item
     ticket = (int)atomicAdd(&p.queue[home], 1u);
@@ -561,42 +561,50 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
       if (run < 64) break;
     }
     nd = __builtin_amdgcn_readfirstlane(nd);
-    // two 8 KB V tiles per wave: waves 0, 1 in the V buffers, waves 2, 3 in the K buffers
-    uint16_t *Vw0 = (wv < 2 ? &Vs[0][0] : &Ks[0][0]) + (wv & 1) * (2 * 32 * 128);
-    const unsigned ldsVw = (unsigned)(uintptr_t)(__attribute__((address_space(3))) uint16_t *)Vw0;
+    // one 8 KB K tile and one 8 KB V tile per wave: waves 0, 1 in the V buffers, waves 2, 3 in the K buffers
+    uint16_t *Kw = (wv < 2 ? &Vs[0][0] : &Ks[0][0]) + (wv & 1) * (2 * 32 * 128);
+    uint16_t *Vw = Kw + 32 * 128;
+    const unsigned ldsKw = (unsigned)(uintptr_t)(__attribute__((address_space(3))) uint16_t *)Kw;
+    const unsigned ldsVw = ldsKw + 32 * 256;
     const int rstar = 4 * (q >> 3) + (q & 3);        // register of S^T that holds key_local == q
     const bool holder = gg == ((q >> 2) & 1);        // ... in this half of the lane pair
-    const int vrow = lane >> 4;                      // V copy: one instruction moves rows 4n + vrow
-    const unsigned vchunk = (unsigned)(((lane & 15) ^ (vrow << 2)) << 4);  // swizzle applied on the global side
-    const unsigned vfast = (unsigned)(vrow * (int)p.kv_rs * 2) + vchunk;
-    const uint16_t *Kq = Kh + 8 * gg;
+    const int vrow = lane >> 4;                      // copies: one instruction moves rows 4n + vrow
+    const unsigned vchunk = (unsigned)(((lane & 15) ^ (vrow << 2)) << 4);  // swizzles applied on the global side
+    // K rows are swizzled by (row & 15) = (4n & 15) ^ vrow: four per-lane offsets serve the eight copies
+    const unsigned kchunk = (unsigned)(((lane & 15) ^ vrow) << 4);
+    const unsigned krow = (unsigned)(vrow * (int)p.kv_rs * 2);
     const uint32_t *kw = wv < 2 ? kept0 : kept1;
-    bf16x8 kd[8];
     uint32_t cw = 0u;
-#define SA_DIAG_ISSUE(o, stg)                                                                    \
+    // The copies of one offset: 32 K rows and 32 V rows, both global -> LDS.  (K used to be read
+    // straight into the operand registers, one row per lane: every quarter-wave of such a read
+    // touches 16 different cache lines, and the L1's tag lookups, 512 per wave and offset, were what
+    // this phase waited for.)
+#define SA_DIAG_COPY(src, o, fastv, chunkv, swzn, ldsb)                                           \
   {                                                                                              \
     const int jb_ = r0 - (o);                                                                    \
-    if (has_cols) cw = bits_window32(colbm, N / 32, jb_);                                        \
-    const int jr_ = min(max(jb_ + q, 0), N - 1);                                                 \
-    const uint16_t *kr_ = Kq + (size_t)jr_ * p.kv_rs;                                            \
-    _Pragma("unroll") for (int k_ = 0; k_ < 8; ++k_) kd[k_] = *(const bf16x8 *)(kr_ + 16 * k_);  \
-    const unsigned lv_ = ldsVw + (stg) * (32 * 256);                                             \
     if (jb_ >= 0 && jb_ + 31 < N) {                                                              \
-      const uint16_t *vb_ = Vh + (size_t)jb_ * p.kv_rs;                                          \
+      const uint16_t *b_ = (src) + (size_t)jb_ * p.kv_rs;                                        \
       _Pragma("unroll") for (int n_ = 0; n_ < 8; ++n_)                                           \
-        SA_DMA16(vb_ + (size_t)(4 * n_) * p.kv_rs, vfast, lv_ + n_ * 1024);                      \
+        SA_DMA16(b_ + (size_t)(4 * n_) * p.kv_rs, (fastv) + ((chunkv) ^ (unsigned)(swzn)), (ldsb) + n_ * 1024); \
     } else { /* rows outside the sequence: clamped copies, masked out by the validity test */    \
       _Pragma("unroll") for (int n_ = 0; n_ < 8; ++n_) {                                         \
         const int rb_ = min(max(jb_ + 4 * n_, 0), N - 1);                                        \
         const int dr_ = min(max(jb_ + 4 * n_ + vrow, 0), N - 1) - rb_; /* >= 0 */                \
-        SA_DMA16(Vh + (size_t)rb_ * p.kv_rs, (unsigned)(dr_ * (int)p.kv_rs * 2) + vchunk,        \
-                 lv_ + n_ * 1024);                                                               \
+        SA_DMA16((src) + (size_t)rb_ * p.kv_rs,                                                  \
+                 (unsigned)(dr_ * (int)p.kv_rs * 2) + ((chunkv) ^ (unsigned)(swzn)), (ldsb) + n_ * 1024); \
       }                                                                                          \
     }                                                                                            \
   }
+#define SA_DIAG_ISSUE_K(o)                                                                       \
+  {                                                                                              \
+    if (has_cols) cw = bits_window32(colbm, N / 32, r0 - (o));                                   \
+    SA_DIAG_COPY(Kh, o, krow, kchunk, ((4 * n_) & 15) << 4, ldsKw)                               \
+  }
+#define SA_DIAG_ISSUE_V(o) SA_DIAG_COPY(Vh, o, (unsigned)(vrow * (int)p.kv_rs * 2), vchunk, 0, ldsVw)
     if (nd > 0) {
       const int o0 = (int)uload(offp, 0);
-      SA_DIAG_ISSUE(o0, 0);
+      SA_DIAG_ISSUE_K(o0);
+      SA_DIAG_ISSUE_V(o0);
     }
     for (int e = 0; e < nd; ++e) {
       const int o = (int)uload(offp, e);
@@ -605,14 +613,17 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
       f32x16 sd;
 #pragma unroll
       for (int r = 0; r < 16; ++r) sd[r] = 0.f;
+      // K of this offset has landed once only the 8 copies of its V, issued after it, are outstanding
+      __builtin_amdgcn_s_waitcnt(0x0F78);  // vmcnt(8)
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) sd = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kd[ks], qf[ks], sd, 0, 0, 0);
+      for (int ks = 0; ks < 8; ++ks)
+        sd = __builtin_amdgcn_mfma_f32_32x32x16_bf16(SA_KFRAG(Kw, 0, ks), qf[ks], sd, 0, 0, 0);
       float sv = sd[0];
 #pragma unroll
       for (int r = 1; r < 16; ++r) sv = (r == rstar) ? sd[r] : sv;
       const bool cbit = (cw >> q) & 1u;
-      // the K registers and the other V tile (last read one offset ago) are free: next offset
-      if (e + 1 < nd) SA_DIAG_ISSUE(onext, (e + 1) & 1);
+      // the K tile has been read into the matrix pipe: the next offset's K may land
+      if (e + 1 < nd) SA_DIAG_ISSUE_K(onext);
       // validity of (query iq, key iq - o)
       const int j = iq - o;
       bool valid = holder && j >= 0 && iq < N;
@@ -642,11 +653,10 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
       const float pv = valid ? __builtin_amdgcn_exp2f(__builtin_fmaf(sv, p.c, -m_ref)) : 0.f;
       l_run += pv;
       const __bf16 pvb = (__bf16)pv, zb = (__bf16)0.f;
-      // V of this offset has landed once only the 16 reads of the next offset, all issued after
-      // it, are outstanding
-      if (e + 1 < nd) __builtin_amdgcn_s_waitcnt(0x4F70);  // vmcnt(16)
+      // V of this offset has landed once only the 8 copies of the next K, issued after it, are
+      // outstanding
+      if (e + 1 < nd) __builtin_amdgcn_s_waitcnt(0x0F78);  // vmcnt(8)
       else __builtin_amdgcn_s_waitcnt(0x0F70);                       // vmcnt(0)
-      const uint16_t *Vw = Vw0 + (e & 1) * (32 * 128);
       // P^T is diagonal: slot e2 of k-step u is register 8u+e2
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
@@ -662,8 +672,12 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
                                                              oacc[db], 0, 0, 0);
         }
       }
+      // the V tile has been read: the next offset's V may land
+      if (e + 1 < nd) SA_DIAG_ISSUE_V(onext);
     }
-#undef SA_DIAG_ISSUE
+#undef SA_DIAG_ISSUE_K
+#undef SA_DIAG_ISSUE_V
+#undef SA_DIAG_COPY
   }
 
   if constexpr (STATS) {  // one pair of atomics per wave and item
