@@ -689,10 +689,14 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
     }
   }
   // ---- epilogue: O[iq][32db + 8(r/4) + 4gg + r%4] = oacc / l -------------------------------------
+  // A lane holds 16 separate 8-byte pieces of its row.  They go through an 8 KB LDS tile of the
+  // wave's own (swizzled like a K tile) and leave as whole 256-byte rows, 16 bytes per lane: 64
+  // cache lines per wave instead of 1024 partial writes.
   const float ltot = l_run + __shfl_xor(l_run, 32);
   const float inv = ltot > 0.f ? 1.f / ltot : 0.f;
-  if (iq < N) {
-    uint16_t *orow = p.O + (size_t)h * p.q_hs + (size_t)iq * p.q_rs;
+  if (!has_offs) __syncthreads();  // the shared tiles are free (with diagonals, that barrier has been passed)
+  {
+    char *ow = (char *)((wv < 2 ? &Vs[0][0] : &Ks[0][0]) + (wv & 1) * (2 * 32 * 128));
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -700,8 +704,18 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
         union { __bf16 b[4]; uint2 u; } o;
 #pragma unroll
         for (int e = 0; e < 4; ++e) o.b[e] = (__bf16)(oacc[db][4 * rb + e] * inv);
-        *(uint2 *)(orow + 32 * db + 8 * rb + 4 * gg) = o.u;
+        *(uint2 *)(ow + q * 256 + (((4 * db + rb) ^ (q & 15)) << 4) + 8 * gg) = o.u;
       }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    const int rr = lane >> 4, pc = lane & 15;
+#pragma unroll
+    for (int n = 0; n < 8; ++n) {
+      const int r = 4 * n + rr;
+      const uint4 v = *(const uint4 *)(ow + r * 256 + (pc << 4));
+      if (r0 + r < N)
+        *(uint4 *)(p.O + (size_t)h * p.q_hs + (size_t)(r0 + r) * p.q_rs + ((pc ^ (r & 15)) << 3)) = v;
+    }
   }
   }  // work-queue loop
 }
