@@ -226,8 +226,8 @@ def run_workload(name, steps, warmup, layers, with_cpu, sample_rows, with_dense=
 
 
 def run_block_rules(name, steps):
-    """The two readings of Alg. 3's TopKBlocks side by side on one layer: one top-k over the whole
-    block map against the same fraction of every row.  Error = Frobenius distance of the sparse
+    """The readings of Alg. 3's TopKBlocks side by side on one layer: one top-k over the whole
+    block map, the same fraction of every row, and one top-k on the row-normalised key.  Error = Frobenius distance of the sparse
     output to the all-keys output of the same kernel, over the Block-Cluster heads."""
     import numpy as np
     import torch
@@ -247,7 +247,8 @@ def run_block_rules(name, steps):
     Q, K, V = up(data["Q"]), up(data["K"]), up(data["V"])
     outs, res = {}, {"workload": name}
     for label, kw in (("all_keys", dict(local_blocks=nb, k_blocks=nb * (nb + 1) // 2)),
-                      ("global", dict(block_select=0)), ("per_row", dict(block_select=1))):
+                      ("global", dict(block_select=0)), ("per_row", dict(block_select=1)),
+                      ("row_normalised", dict(block_select=2))):
         ses = sa.Session(Hq, Hkv, N, b, w, keep=wl.keep, **kw)
         O = torch.empty_like(Q)
         ov = [sa.SA_TRIANGULAR] * Hq if label == "all_keys" else None
@@ -268,10 +269,10 @@ def run_block_rules(name, steps):
                       "kept_pairs": int(kept), "tiles": int(tiles)}
         ses.close()
     pat = outs["global"][1]
-    assert (pat == outs["per_row"][1]).all()
+    assert (pat == outs["per_row"][1]).all() and (pat == outs["row_normalised"][1]).all()
     bc = np.nonzero(pat == sa.SA_BLOCK_CLUSTER)[0]
     ref = outs["all_keys"][0].float()
-    for label in ("global", "per_row"):
+    for label in ("global", "per_row", "row_normalised"):
         diff = (outs[label][0].float() - ref)[torch.from_numpy(bc).to(dev)]
         err = torch.linalg.vector_norm(diff.double(), dim=(1, 2)).cpu().numpy()
         res[label]["block_cluster_heads"] = bc.tolist()

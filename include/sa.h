@@ -66,8 +66,11 @@ typedef enum {
  *   SA_BLOCKS_GLOBAL   one top-k over all causal blocks of the head (the literal reading);
  *   SA_BLOCKS_PER_ROW  row block R keeps min(R+1, ceil(k_blocks (R+1) / (nb (nb+1)/2))) blocks:
  *                      its diagonal block and its best lower blocks, ties to the lower block id,
- *                      i.e. the same fraction of every row (at most nb blocks above k_blocks). */
-typedef enum { SA_BLOCKS_GLOBAL = 0, SA_BLOCKS_PER_ROW = 1 } sa_block_select;
+ *                      i.e. the same fraction of every row (at most nb blocks above k_blocks);
+ *   SA_BLOCKS_GLOBAL_ROW_NORMALISED  one top-k like SA_BLOCKS_GLOBAL, on the key blk[R][C] * (R+1)
+ *                      (one fp32 multiplication): an entry is measured against the uniform value
+ *                      1/(R+1) of its own softmax row, so short early rows no longer win by construction. */
+typedef enum { SA_BLOCKS_GLOBAL = 0, SA_BLOCKS_PER_ROW = 1, SA_BLOCKS_GLOBAL_ROW_NORMALISED = 2 } sa_block_select;
 
 /* Granularity of the selected diagonals of an Interval-Slash head (Alg. 2 combines vertical and
  * slash indices but does not say at which granularity the kernel applies them):

@@ -51,7 +51,8 @@ class Budgets:
     probe_s: int = 4
     lift_num: int = 4
     lift_den: int = 1
-    block_select: int = 0   # 0: one global top-k over the block map, 1: the same fraction of every row
+    block_select: int = 0   # 0: one global top-k over the block map, 1: the same fraction of every row,
+                            # 2: global top-k on the row-normalised key blk[R][C] * (R + 1)
     diagonal_select: int = 0  # 0: element-exact diagonals, 1: every selected diagonal widened to blocks
 
 

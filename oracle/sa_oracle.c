@@ -369,6 +369,7 @@ static int choose_pattern(const float *v, const float *s, int N, int b, int w, i
  * the same step): row R keeps keep(R) = min(R+1, ceil(k_blocks (R+1) / (nb (nb+1)/2)))
  * blocks: its diagonal block and the keep(R)-1 largest blk[R][C], C<R (ties to
  * the lower C), i.e. every row block gets the same fraction of its causal blocks.
+ * block_select 2: the global top-k again, on the row-normalised key blk[R][C] * (R+1).
  * diagonal_select 1 (diagonals at block granularity instead of element-exact):
  * an Interval-Slash head keeps, for every selected offset o and every query i >= o,
  * the whole block pair (i / b, (i - o) / b); the offsets are then part of the CSR
@@ -380,7 +381,7 @@ int oracle_build_index(const float *v, const float *s, const float *blk, int Hq,
                        int32_t *cols, int32_t *n_offs, int32_t *offs, int32_t *rowptr,
                        int32_t *blkcols, int block_select, int diagonal_select) {
   if (N % b) return 1;
-  if (block_select != 0 && block_select != 1) return 1;
+  if (block_select < 0 || block_select > 2) return 1;
   if (diagonal_select != 0 && diagonal_select != 1) return 1;
   const int nb = N / b;
   int err = 0;
@@ -433,7 +434,13 @@ int oracle_build_index(const float *v, const float *s, const float *blk, int Hq,
       int32_t *ix = (int32_t *)malloc(sizeof(int32_t) * (size_t)(ncand > 0 ? ncand : 1));
       int t = 0;
       for (int R = 0; R < nb; ++R)
-        for (int C = 0; C < R; ++C) { sc[t] = bh[(size_t)R * nb + C]; ix[t] = R * nb + C; ++t; }
+        for (int C = 0; C < R; ++C) {
+          /* block_select 2: the key is the entry times the length R+1 of its softmax row (one
+           * fp32 multiplication), so that short early rows do not outrank long ones by construction */
+          sc[t] = block_select == 2 ? bh[(size_t)R * nb + C] * (float)(R + 1) : bh[(size_t)R * nb + C];
+          ix[t] = R * nb + C;
+          ++t;
+        }
       int k = k_blocks - nb;
       if (k < 0) k = 0;
       int32_t *sel = (int32_t *)malloc(sizeof(int32_t) * (size_t)(k > 0 ? k : 1));

@@ -92,7 +92,7 @@ sa_status sa_create(const sa_config *cfg, sa_ctx **out) {
   if (cfg->k_vertical < 1 || cfg->k_slash < 1 || cfg->k_blocks < nb) return SA_ERR_INVALID_ARG;
   if (cfg->probe_v < 0 || cfg->probe_s < 0 || cfg->lift_num < 0 || cfg->lift_den < 0) return SA_ERR_INVALID_ARG;
   if (cfg->softmax_scale < 0.f) return SA_ERR_INVALID_ARG;
-  if (cfg->block_select != SA_BLOCKS_GLOBAL && cfg->block_select != SA_BLOCKS_PER_ROW) return SA_ERR_INVALID_ARG;
+  if (cfg->block_select < SA_BLOCKS_GLOBAL || cfg->block_select > SA_BLOCKS_GLOBAL_ROW_NORMALISED) return SA_ERR_INVALID_ARG;
   if (cfg->diagonal_select != SA_DIAGONALS_EXACT && cfg->diagonal_select != SA_DIAGONALS_BLOCKS) return SA_ERR_INVALID_ARG;
 
   sa_ctx *c = new (std::nothrow) sa_ctx();
@@ -109,6 +109,7 @@ sa_status sa_create(const sa_config *cfg, sa_ctx **out) {
   s.lift_den = cfg->lift_den ? cfg->lift_den : 1;
   const long long tri = triangular_count(nb, s.sink, s.local);
   s.row_select = cfg->block_select == SA_BLOCKS_PER_ROW;
+  s.row_norm = cfg->block_select == SA_BLOCKS_GLOBAL_ROW_NORMALISED;
   // the per-row rule rounds every row's share up: at most one block per row above k_b
   const long long kcap = (long long)s.k_b + (s.row_select ? nb : 0);
   long long cap = tri > kcap ? tri : kcap;

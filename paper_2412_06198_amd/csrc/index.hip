@@ -123,9 +123,11 @@ __device__ inline void wave_visit4(const unsigned *p, int lo, int hi, bool vec, 
 // map, walked by one wave in units of 1024 keys with the next unit's loads issued before the
 // current one is processed: short rows would otherwise expose one memory round trip each.
 // begin(R) / end(R) bracket a row.
+// With scale_rows the key of an entry of row R is its value times R + 1 (one fp32 multiplication;
+// all values are >= +0, so the products order like their bit patterns too).
 template <class Begin, class Fn, class End>
 __device__ inline void wave_rows_visit4(const unsigned *blk, int nb, int first, int stride, bool vec,
-                                        Begin begin, Fn fn, End end) {
+                                        bool scale_rows, Begin begin, Fn fn, End end) {
   constexpr int U = 4;
   const int lane = threadIdx.x & 63;
   int R = first, c0 = 0;    // unit being processed
@@ -147,6 +149,13 @@ __device__ inline void wave_rows_visit4(const unsigned *blk, int nb, int first, 
     advance(Rn, cn);
     if (Rn < nb) load_unit(nxt, Rn, cn);
     if (c0 == 0) begin(R);
+    if (scale_rows) {
+      const float len = (float)(R + 1);
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) cur[u].k[j] = __float_as_uint(__uint_as_float(cur[u].k[j]) * len);
+    }
 #pragma unroll
     for (int u = 0; u < U; ++u)
       if (c0 + 256 * u < R) fn(cur[u], c0 + 256 * u + 4 * lane, R);
@@ -326,7 +335,7 @@ __global__ __launch_bounds__(BT) void idx_hist_kernel(IdxArgs a) {
   });
   if (do_vs) wave_visit4(sb, lo, hi, true, [&](const Keys4 &v, int i0, int lim) { visit(v, i0, lim, 1); });
   if (do_blk)
-    wave_rows_visit4(bb, nb, gw, a.PW, (nb & 3) == 0, [](int) {},
+    wave_rows_visit4(bb, nb, gw, a.PW, (nb & 3) == 0, sh.row_norm != 0, [](int) {},
                      [&](const Keys4 &v, int i0, int lim) { visit(v, i0, lim, 2); }, [](int) {});
   __syncthreads();
   unsigned *gh = LEVEL == 1 ? &G->hist1[0][0] : (LEVEL == 2 ? &G->hist2[0][0] : &G->hist3[0][0]);
@@ -424,7 +433,7 @@ __global__ __launch_bounds__(BT) void idx_count_kernel(IdxArgs a) {
   if (!sh.row_select && (a.mask & 2)) {
     unsigned gt = 0, eq = 0;
     wave_rows_visit4(
-        bb, nb, gw, a.PW, (nb & 3) == 0, [&](int) { gt = 0; eq = 0; },
+        bb, nb, gw, a.PW, (nb & 3) == 0, sh.row_norm != 0, [&](int) { gt = 0; eq = 0; },
         [&](const Keys4 &v, int i0, int lim) {
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
@@ -628,7 +637,7 @@ __global__ __launch_bounds__(BT) void idx_emit_kernel(IdxArgs a) {
     const unsigned thr = G->thr[4], need = G->need[4];
     unsigned grun = 0, erun = 0;
     wave_rows_visit4(
-        a.blk + (size_t)h * nb * nb, nb, gw, a.PW, (nb & 3) == 0,
+        a.blk + (size_t)h * nb * nb, nb, gw, a.PW, (nb & 3) == 0, sh.row_norm != 0,
         [&](int R) { grun = G->rowgt[R]; erun = G->roweq[R]; },
         [&](const Keys4 &v, int i0, int lim) {
           // lim is the row index R: a selected entry lands after the R diagonals of the rows above

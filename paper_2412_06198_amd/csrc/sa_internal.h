@@ -20,6 +20,7 @@ struct Shape {
   int k_v, k_s, k_b, cap_b, sink, local;
   int probe_v, probe_s, lift_num, lift_den;
   int row_select;                 // Block-Cluster heads: 1 = every row keeps its own share of k_b
+  int row_norm;                   // Block-Cluster heads: 1 = global top-k on blk[R][C] * (R + 1)
   int diag_blocks;                // Interval-Slash heads: 1 = selected diagonals kept as whole blocks
   int chunk, nchunks;             // keys per estimator workgroup (window passes), ceil(N / chunk)
   int n_cu;                       // compute units of the device the context was created on

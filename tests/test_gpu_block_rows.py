@@ -122,3 +122,34 @@ def test_per_row_whole_path_at_cfg5_128k():
     ref, ws, _ = orc.masked_rows(data["Q"], data["K"], data["V"], b, got, rows=rows)
     assert np.abs(ws - 1).max() < 1e-9
     check_attention(host_f64(O[:, torch.from_numpy(rows.astype(np.int64)).cuda()]), ref, "per-row cfg5")
+
+
+@pytest.mark.parametrize("N,b,keep", [(4096, 64, 0.10), (2048, 128, 0.3)])
+def test_row_normalised_key_index_bit_exact(N, b, keep):
+    # block_select 2: the global top-k on blk[R][C] * (R + 1), both sides one fp32 multiplication
+    print(f"case row-normalised key N={N} b={b}", flush=True)
+    wl = gen.scaled(gen.WORKLOADS["cfg3"], name="t", n_q_heads=8, n_kv_heads=2, seq_len=N,
+                    block=b, seed=N + 5, n_hot=8, hot_block=b, keep=keep)
+    data = gen.generate(wl)
+    bud = dataclasses.replace(orc.default_budgets(N, b, keep), block_select=2)
+    ses = make_session(8, 2, N, b, 64, bud)
+    ses.estimate(dev_bf16(data["Q"]), dev_bf16(data["K"]))
+    v, s, blk = download_scores(ses)
+    for ov in (None, [BC] * 8):
+        ses.build_index(ov)
+        got = download_index(ses)
+        assert_index_equal(got, orc.build_index(v, s, blk, N, b, 64, bud, override=ov))
+    plain = orc.build_index(v, s, blk, N, b, 64, dataclasses.replace(bud, block_select=0), override=[BC] * 8)
+    assert got.blkcols.tobytes() != plain.blkcols.tobytes()       # the key does change the choice
+    # heavy ties after scaling: small integers over powers of two
+    Hq, N2, b2 = 4, 1024, 64
+    nb = N2 // b2
+    rng = np.random.default_rng(12)
+    v2 = rng.random((Hq, N2), dtype=np.float32)
+    blk2 = (np.tril(rng.integers(0, 4, (Hq, nb, nb))) / 2.0 ** rng.integers(0, 3, (Hq, nb, 1))).astype(np.float32)
+    for kb in (nb + 1, nb + 33, nb * (nb + 1) // 2):
+        bud2 = orc.Budgets(1, 2, 16, 4, kb, block_select=2)
+        ses2 = make_session(Hq, 2, N2, b2, 64, bud2)
+        upload_scores(ses2, v2, v2, blk2)
+        ses2.build_index([BC] * Hq)
+        assert_index_equal(download_index(ses2), orc.build_index(v2, v2, blk2, N2, b2, 64, bud2, override=[BC] * Hq))

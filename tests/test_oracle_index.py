@@ -213,6 +213,40 @@ def test_block_widened_diagonals_special_cases():
         assert all(x.tobytes() == y.tobytes() for x, y in zip(a.arrays()[:6], c.arrays()[:6]))
 
 
+@settings(max_examples=30, deadline=None)
+@given(st.lists(st.integers(0, 6), min_size=36, max_size=36), st.integers(6, 21), st.integers(0, 3))
+def test_row_normalised_block_key_is_the_global_rule_on_the_scaled_map(vals, kb, seed):
+    # block_select 2 must select what the (already pinned) global rule selects on blk[R][C] * (R+1),
+    # the scaling done here in numpy float32
+    nb, b = 6, 4
+    N = nb * b
+    rng = np.random.default_rng(seed)
+    blk = (np.array(vals, np.float32).reshape(1, nb, nb) * np.float32(0.125)
+           + rng.random((1, nb, nb)).astype(np.float32) * np.float32(seed > 0))
+    v = np.ones((1, N), np.float32)
+    scaled = (blk * np.arange(1, nb + 1, dtype=np.float32)[None, :, None]).astype(np.float32)
+    a = orc.build_index(v, v, blk, N, b, 4, _bud(k_blocks=kb, block_select=2), override=[BC])
+    c = orc.build_index(v, v, scaled, N, b, 4, _bud(k_blocks=kb, block_select=0), override=[BC])
+    assert all(x.tobytes() == y.tobytes() for x, y in zip(a.arrays(), c.arrays()))
+
+
+def test_row_normalised_block_key_prefers_relative_peaks():
+    # a block that is 3x its row's uniform value in a long row against one that is 1.5x in a short
+    # row: the raw rule takes the short row's (larger absolute value), the normalised one the other
+    nb, b = 8, 4
+    N = nb * b
+    blk = np.zeros((1, nb, nb), np.float32)
+    for R in range(nb):
+        blk[0, R, :R + 1] = 1.0 / (R + 1)
+    blk[0, 1, 0] = 1.5 / 2          # 0.75
+    blk[0, 7, 2] = 3.0 / 8          # 0.375
+    v = np.ones((1, N), np.float32)
+    raw = orc.build_index(v, v, blk, N, b, 4, _bud(k_blocks=nb + 1, block_select=0), override=[BC])
+    nrm = orc.build_index(v, v, blk, N, b, 4, _bud(k_blocks=nb + 1, block_select=2), override=[BC])
+    assert _csr_pairs(raw, 0, nb) - {(R, R) for R in range(nb)} == {(1, 0)}
+    assert _csr_pairs(nrm, 0, nb) - {(R, R) for R in range(nb)} == {(7, 2)}
+
+
 def test_k_larger_than_candidates_is_clamped():
     N, b = 16, 4
     v = np.arange(16, dtype=np.float32)[None]
