@@ -28,7 +28,7 @@ def _draw(rng):
         k_vertical=int(rng.integers(1, min(N, 300) + 1)), k_slash=int(rng.integers(1, min(N, 40) + 1)),
         k_blocks=int(rng.integers(nb, all_blocks + 1)), probe_v=int(rng.integers(1, 7)),
         probe_s=int(rng.integers(1, 7)), lift_num=int(rng.integers(1, 6)), lift_den=int(rng.integers(1, 3)),
-        block_select=int(rng.integers(0, 2)), diagonal_select=int(rng.integers(0, 2)))
+        block_select=int(rng.integers(0, 3)), diagonal_select=int(rng.integers(0, 2)))
     Hq = Hkv * g
     ov = None if rng.random() < 0.4 else [int(x) for x in rng.integers(-1, 3, Hq)]
     return Hq, Hkv, N, b, w, bud, ov
