@@ -607,12 +607,21 @@ __global__ __launch_bounds__(64 * kMapWaves, (MT <= 8 ? 4 : 2)) void block_map_k
       }
     }
   }
-  // zeros right of the strip's last tile
+  // zeros right of the strip's last tile (16 bytes per lane where the rows allow it)
   const int c0 = 16 * T;
-  for (int r = 0; r < 16; ++r) {
-    const int R = R0 + r;
-    if (R >= nb) break;
-    for (int C = c0 + tid; C < nb; C += 64 * kMapWaves) dst[(size_t)R * nb + C] = 0.f;
+  if ((nb & 3) == 0) {
+    const int n4 = (nb - c0) >> 2, rows = min(16, nb - R0);
+    const float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int i = tid; i < rows * n4; i += 64 * kMapWaves) {
+      const int r = i / n4, c4 = i - r * n4;
+      *(float4 *)(dst + (size_t)(R0 + r) * nb + c0 + 4 * c4) = z4;
+    }
+  } else {
+    for (int r = 0; r < 16; ++r) {
+      const int R = R0 + r;
+      if (R >= nb) break;
+      for (int C = c0 + tid; C < nb; C += 64 * kMapWaves) dst[(size_t)R * nb + C] = 0.f;
+    }
   }
 }
 
