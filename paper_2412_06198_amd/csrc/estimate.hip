@@ -49,9 +49,9 @@ __device__ inline void store_split(float *means_head, int R, int d, float x) {
 // ------------------------------------------------------------------ Q block means
 // grid (nb, Hq), 256 threads: thread = (row group of 16, 16-byte column); all RPT = b/16 loads of
 // a thread are in flight before the first sum.  The kernel is pure HBM streaming and runs beside
-// the window passes (vector ALU bound): it is launched with kQMeanLdsPad bytes of unused dynamic
+// the window passes (vector ALU bound): it is launched with kQMeanLdsPad* bytes of unused dynamic
 // LDS so that it never holds more than a few wave slots of a compute unit.
-constexpr int kQMeanLdsPad = 24 * 1024;
+constexpr int kQMeanLdsPad128 = 40 * 1024, kQMeanLdsPad64 = 32 * 1024;  // by block size: measured best
 
 template <int RPT>
 __global__ __launch_bounds__(256) void q_block_mean_kernel(const uint16_t *__restrict__ Q, Shape sh,
@@ -647,9 +647,9 @@ hipError_t launch_estimate(const Shape &sh, const Workspace &ws, const uint16_t 
     sq = fk.aux;
   }
   if (sh.b == 128)
-    q_block_mean_kernel<8><<<dim3(sh.nb, sh.Hq), 256, kQMeanLdsPad, sq>>>(Q, sh, ws.qblk);
+    q_block_mean_kernel<8><<<dim3(sh.nb, sh.Hq), 256, kQMeanLdsPad128, sq>>>(Q, sh, ws.qblk);
   else
-    q_block_mean_kernel<4><<<dim3(sh.nb, sh.Hq), 256, kQMeanLdsPad, sq>>>(Q, sh, ws.qblk);
+    q_block_mean_kernel<4><<<dim3(sh.nb, sh.Hq), 256, kQMeanLdsPad64, sq>>>(Q, sh, ws.qblk);
   const dim3 wgrid(sh.nchunks, sh.Hkv, (sh.g + 3) / 4);
   window_stats_kernel<<<wgrid, 256, 0, st>>>(Q, K, sh, c, ws.part, out.s, ws.kblk);
   if (fk.aux) {  // the block map needs the K block means of the stats pass
