@@ -66,7 +66,20 @@ struct IdxArgs {
   // Which part of the work a launch does: bit 0 = the selections on v and s, bit 1 = the selection
   // on the block map (the two parts touch disjoint fields of the scratch and may run side by side).
   int mask;
+  // Heads (bit h) whose pattern override makes the v/s selections, or the block selection, unnecessary.
+  uint32_t skip_vs[kMaxHeads / 32], skip_blk[kMaxHeads / 32];
 };
+
+// Whether a launch has to touch one part of a head's work (the selections on v and s, or the one on
+// the block map): with a pattern override only the overridden pattern's own selection is needed,
+// none for Triangular.  (Skipping the rest of a head as soon as it passes the Triangular test was
+// tried too: the flag costs every later workgroup one more dependent read, more than it saves.)
+__device__ inline bool head_wants(const IdxArgs &a, int h, bool blk_part) {
+  const int w = h >> 5;  // four words: selected without indexing the argument block dynamically
+  const uint32_t *m = blk_part ? a.skip_blk : a.skip_vs;
+  const uint32_t bits = w == 0 ? m[0] : w == 1 ? m[1] : w == 2 ? m[2] : m[3];
+  return !((bits >> (h & 31)) & 1u);
+}
 
 // floor(x * 2^30) of a finite fp32 x >= 0 given by its bits.
 __device__ inline unsigned long long fx30(unsigned bits) {
@@ -76,6 +89,47 @@ __device__ inline unsigned long long fx30(unsigned bits) {
   const int sh = e - 120;   // (e - 127) - 23 + 30
   if (sh >= 0) return sh < 40 ? (m << sh) : ~0ull;
   return (-sh) < 64 ? (m >> (-sh)) : 0ull;
+}
+
+// The Triangular test of the pattern rule on the sums of the level-1 histogram launch; E receives
+// the number of causal window entries.
+__device__ inline bool triangular_test(const IdxArgs &a, const IdxScratch *G, unsigned long long &E) {
+  const Shape &sh = a.sh;
+  const int N = sh.N, nb = sh.nb;
+  long long sbnd = (long long)sh.sink * sh.b;
+  if (sbnd > N) sbnd = N;
+  long long lb0 = (long long)(nb - sh.local) * sh.b;
+  if (lb0 < sbnd) lb0 = sbnd;
+  unsigned long long ET = 0;
+  E = 0;
+  for (int i = 0; i < sh.w; ++i) {
+    const long long qi1 = (long long)N - sh.w + i + 1;
+    E += (unsigned long long)qi1;
+    ET += (unsigned long long)(qi1 < sbnd ? qi1 : sbnd);
+    if (qi1 > lb0) ET += (unsigned long long)(qi1 - lb0);
+  }
+  typedef unsigned __int128 u128;
+  return (u128)sh.lift_den * G->ct * E >= (u128)sh.lift_num * G->vtot * ET;
+}
+
+// Pattern of head h: the caller's override, else the integer lift tests on the sums that the level-1
+// histogram launch (vtot, ct) and the counting launch (topsum) left in the scratch.
+__device__ inline int decide_pattern(const IdxArgs &a, const IdxScratch *G, int h) {
+  const Shape &sh = a.sh;
+  const int pat = a.ov.pat[h];
+  if (pat >= 0) return pat;
+  unsigned long long E;
+  if (triangular_test(a, G, E)) return SA_TRIANGULAR;
+  typedef unsigned __int128 u128;
+  // sum over the probe best = sum over keys above the threshold + ties at the threshold
+  const unsigned long long sv =
+      a.ksel[0] > 0 ? G->topsum[0] + (unsigned long long)G->need[0] * fx30(G->thr[0]) : 0ull;
+  const unsigned long long ss =
+      a.ksel[1] > 0 ? G->topsum[1] + (unsigned long long)G->need[1] * fx30(G->thr[1]) : 0ull;
+  if ((u128)sh.lift_den * (sv + ss) * E >=
+      (u128)sh.lift_num * G->vtot * (unsigned long long)(sh.probe_v + sh.probe_s) * (unsigned long long)sh.w)
+    return SA_INTERVAL_SLASH;
+  return SA_BLOCK_CLUSTER;
 }
 
 // Blocks that row block R keeps under the per-row rule: the same fraction k_b / (nb (nb+1) / 2) of
@@ -280,7 +334,8 @@ __global__ __launch_bounds__(BT) void idx_hist_kernel(IdxArgs a) {
   const int p = blockIdx.x, h = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int N = sh.N, nb = sh.nb;
   IdxScratch *G = a.scratch + h;
-  const bool do_vs = a.mask & 1, do_blk = (a.mask & 2) && a.ksel[4] > 0;
+  const bool do_vs = (a.mask & 1) && head_wants(a, h, false);
+  const bool do_blk = (a.mask & 2) && a.ksel[4] > 0 && head_wants(a, h, true);
   if (!do_vs && !do_blk) return;
   const unsigned *vb = a.v + (size_t)h * N, *sb = a.s + (size_t)h * N;
   const unsigned *bb = a.blk + (size_t)h * nb * nb;
@@ -372,7 +427,7 @@ __global__ __launch_bounds__(BT) void idx_select_kernel(IdxArgs a) {
     *(uint4 *)&(&hist[0][0])[i] = *(const uint4 *)&gh[i];
   __syncthreads();
   for (int q = wv; q < NSEL; q += WPB) {  // wave w takes selections w and w + 4
-    if (!(a.mask & (q < 4 ? 1 : 2))) continue;
+    if (!(a.mask & (q < 4 ? 1 : 2)) || !head_wants(a, h, q == 4)) continue;
     if (a.ksel[q] <= 0) {
       if (LEVEL == 3 && lane == 0) { G->thr[q] = 0xFFFFFFFFu; G->need[q] = 0u; }
       continue;
@@ -411,7 +466,7 @@ __global__ __launch_bounds__(BT) void idx_count_kernel(IdxArgs a) {
   for (int q = 0; q < NSEL; ++q) { thr[q] = G->thr[q]; need[q] = G->need[q]; }
   const int gw = p * WPB + wv;
   const int lo = min(gw * a.seg, N), hi = min(lo + a.seg, N);
-  const bool do_vs = a.mask & 1;
+  const bool do_vs = (a.mask & 1) && head_wants(a, h, false);
   for (int arr = 0; arr < 2 && do_vs; ++arr) {
     unsigned gt = 0, eq = 0;
     unsigned long long ts = 0;
@@ -430,7 +485,7 @@ __global__ __launch_bounds__(BT) void idx_count_kernel(IdxArgs a) {
     }
     if (lane == 0) { G->wgt[arr][gw] = gt; G->weq[arr][gw] = eq; red64[arr][wv] = ts; }
   }
-  if (!sh.row_select && (a.mask & 2)) {
+  if (!sh.row_select && (a.mask & 2) && head_wants(a, h, true)) {
     unsigned gt = 0, eq = 0;
     wave_rows_visit4(
         bb, nb, gw, a.PW, (nb & 3) == 0, sh.row_norm != 0, [&](int) { gt = 0; eq = 0; },
@@ -453,38 +508,6 @@ __global__ __launch_bounds__(BT) void idx_count_kernel(IdxArgs a) {
     for (int w = 0; w < WPB; ++w) t += red64[tid][w];
     atomicAdd(&G->topsum[tid], t);
   }
-}
-
-// Pattern of head h: the caller's override, else the integer lift tests on the sums that the level-1
-// histogram launch (vtot, ct) and the counting launch (topsum) left in the scratch.
-__device__ inline int decide_pattern(const IdxArgs &a, const IdxScratch *G, int h) {
-  const Shape &sh = a.sh;
-  const int N = sh.N, nb = sh.nb;
-  int pat = a.ov.pat[h];
-  if (pat >= 0) return pat;
-  long long sbnd = (long long)sh.sink * sh.b;
-  if (sbnd > N) sbnd = N;
-  long long lb0 = (long long)(nb - sh.local) * sh.b;
-  if (lb0 < sbnd) lb0 = sbnd;
-  unsigned long long E = 0, ET = 0;
-  for (int i = 0; i < sh.w; ++i) {
-    const long long qi1 = (long long)N - sh.w + i + 1;
-    E += (unsigned long long)qi1;
-    ET += (unsigned long long)(qi1 < sbnd ? qi1 : sbnd);
-    if (qi1 > lb0) ET += (unsigned long long)(qi1 - lb0);
-  }
-  const unsigned long long vt = G->vtot, ct = G->ct;
-  typedef unsigned __int128 u128;
-  if ((u128)sh.lift_den * ct * E >= (u128)sh.lift_num * vt * ET) return SA_TRIANGULAR;
-  // sum over the probe best = sum over keys above the threshold + ties at the threshold
-  const unsigned long long sv =
-      a.ksel[0] > 0 ? G->topsum[0] + (unsigned long long)G->need[0] * fx30(G->thr[0]) : 0ull;
-  const unsigned long long ss =
-      a.ksel[1] > 0 ? G->topsum[1] + (unsigned long long)G->need[1] * fx30(G->thr[1]) : 0ull;
-  if ((u128)sh.lift_den * (sv + ss) * E >=
-      (u128)sh.lift_num * vt * (unsigned long long)(sh.probe_v + sh.probe_s) * (unsigned long long)sh.w)
-    return SA_INTERVAL_SLASH;
-  return SA_BLOCK_CLUSTER;
 }
 
 // One workgroup per head: pattern decision, prefixes of the per-part and per-row counts, rowptr.
@@ -805,6 +828,13 @@ IdxArgs index_args(const Shape &sh, const Workspace &ws, sa_scores in, const Ove
   a.ksel[3] = sh.k_s < sh.N ? sh.k_s : sh.N;
   a.ksel[4] = sh.row_select ? 0 : (int)kb;   // per-row rule: selected row by row while emitting
   a.mask = 3;
+  static_assert(kMaxHeads == 128, "four mask words");
+  for (int w = 0; w < kMaxHeads / 32; ++w) a.skip_vs[w] = a.skip_blk[w] = 0u;
+  for (int h = 0; h < sh.Hq; ++h) {
+    const int p = ov.pat[h];
+    if (p >= 0 && p != SA_INTERVAL_SLASH) a.skip_vs[h >> 5] |= 1u << (h & 31);
+    if (p >= 0 && p != SA_BLOCK_CLUSTER) a.skip_blk[h >> 5] |= 1u << (h & 31);
+  }
   return a;
 }
 
