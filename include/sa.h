@@ -8,8 +8,9 @@
  *      columns, diagonals and blocks (sa_build_index),
  *   3. runs causal softmax attention over the selected entries only
  *      (sa_sparse_prefill).
- * Beside this path: one decode step over the same index (sa_sparse_decode)
- * and the offline per-head pattern search (sa_search_patterns).
+ * Beside this path: steps 1 and 2 as one call (sa_estimate_and_index), one
+ * decode step over the same index (sa_sparse_decode) and the offline per-head
+ * pattern search (sa_search_patterns).
  *
  * Conventions
  *   - C99 types only.  Q, K, V, O are DEVICE pointers to raw bf16 (16-bit)
@@ -19,7 +20,7 @@
  *     allocates or frees device memory and never synchronises the host: the
  *     compute calls enqueue kernels on the given HIP stream and return (the
  *     offline search is the exception: the host steers it, see there).
- *     sa_estimate_patterns runs part of its kernels on a side stream that the
+ *     sa_estimate_patterns (and sa_estimate_and_index) runs part of its kernels on a side stream that the
  *     context owns (created by sa_create, default priority); that stream waits
  *     for the given stream at entry and the given stream waits for it at exit,
  *     so work enqueued on the given stream before and after the call is
