@@ -34,7 +34,7 @@ def _draw(rng):
     return Hq, Hkv, N, b, w, bud, ov
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", range(64))
 def test_random_configuration(seed):
     rng = np.random.default_rng(1000 + seed)
     Hq, Hkv, N, b, w, bud, ov = _draw(rng)
