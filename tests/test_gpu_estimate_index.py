@@ -21,7 +21,8 @@ def _check_scores(got, ref, w):
 
 @pytest.mark.parametrize("Hq,Hkv,N,b,w", [(4, 2, 1024, 64, 64), (4, 4, 768, 128, 64),
                                           (8, 2, 2048 + 64, 64, 17), (2, 2, 64, 64, 64),
-                                          (6, 1, 512, 128, 33), (4, 2, 273 * 64, 64, 64)])
+                                          (6, 1, 512, 128, 33), (4, 2, 273 * 64, 64, 64),
+                                          (4, 2, 521 * 64, 64, 64), (2, 1, 261 * 128, 128, 40)])
 def test_scores_match_oracle(Hq, Hkv, N, b, w):
     print(f"case scores Hq={Hq} Hkv={Hkv} N={N} b={b} w={w}", flush=True)
     Q, K, _ = gen.random_qkv(Hq, Hkv, N, 128, seed=N + w)
