@@ -80,6 +80,14 @@ def test_cfg5_128k_one_layer():
     _whole_path("cfg5", 48)
 
 
+def test_ragged_33k_whole_path():
+    # 521 blocks of 64: the last 1024-key chunk of the estimator, the last 128-row item of the
+    # attention kernel and the last 16-row strip of the block map are all partial
+    wl = gen.scaled(gen.WORKLOADS["cfg3"], name="ragged33k", seq_len=521 * 64, block=64, n_q_heads=8,
+                    n_kv_heads=2, keep=0.06, hot_block=64, seed=9100)
+    _whole_path("ragged33k", 64, wl=wl)
+
+
 def test_longest_supported_sequence_256k():
     # the library's limit: 262144 tokens, block 64 (4096 key tiles, the widest tile-list entries),
     # one KV head (all eight work queues on one head), one head per pattern
