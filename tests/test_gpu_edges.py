@@ -126,7 +126,8 @@ def test_empty_index_parts():
 
 
 @pytest.mark.parametrize("Hq,Hkv,N,b", [(3, 3, 704, 64), (10, 5, 640, 128), (6, 1, 576, 64),
-                                        (16, 16, 384, 128), (12, 6, 1088, 64)])
+                                        (16, 16, 384, 128), (12, 6, 1088, 64), (64, 8, 512, 64),
+                                        (40, 5, 384, 128), (128, 16, 256, 64), (9, 9, 448, 64)])
 def test_head_counts_off_the_queue_grid(Hq, Hkv, N, b):
     # KV head counts that do not divide the eight work queues (and row-block counts that do not
     # divide the queues of a KV head): every (head, row block) must still be computed exactly once
