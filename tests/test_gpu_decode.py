@@ -13,11 +13,11 @@ from gpu_util import dev_bf16, download_index, host_f64
 pytestmark = pytest.mark.gpu
 
 
-def _case(Hq, Hkv, N, b, w, extra, keep, override, positions, seed):
-    print(f"case decode Hq={Hq} Hkv={Hkv} N={N} b={b} extra={extra}", flush=True)
+def _case(Hq, Hkv, N, b, w, extra, keep, override, positions, seed, **options):
+    print(f"case decode Hq={Hq} Hkv={Hkv} N={N} b={b} extra={extra} {options}", flush=True)
     Q, K, V = gen.random_qkv(Hq, Hkv, N + extra, 128, seed=seed)
     ses = sa.Session(Hq, Hkv, N, b, w, keep=keep, q_head_stride=(N + extra) * 128,
-                     kv_head_stride=(N + extra) * 128)
+                     kv_head_stride=(N + extra) * 128, **options)
     Qd, Kd, Vd = dev_bf16(Q), dev_bf16(K), dev_bf16(V)
     ses.estimate(Qd, Kd)
     ses.build_index(override)
@@ -39,6 +39,14 @@ def test_decode_patterns_and_positions():
     # every pattern, first and later decode positions, a ragged key list (not a multiple of 16 x splits)
     _case(6, 2, 1024, 64, 64, 9, 0.2, [h % 3 for h in range(6)], [1024, 1027, 1032], 301)
     _case(4, 4, 640, 128, 32, 2, 0.3, [1, 1, 2, 0], [640, 641], 302)
+
+
+@pytest.mark.parametrize("options", [dict(diagonal_select=1), dict(block_select=1), dict(block_select=2),
+                                     dict(block_select=1, diagonal_select=1)])
+def test_decode_over_the_selection_options(options):
+    # the decode step reads whatever index the prefill built: block-granular diagonals (no offset
+    # list, their blocks in the last row's CSR), per-row block budgets, the row-normalised key
+    _case(6, 2, 1152, 64, 64, 5, 0.2, [h % 3 for h in range(6)], [1152, 1156], 311, **options)
 
 
 def test_decode_auto_patterns_planted():
