@@ -71,3 +71,25 @@ def test_search_on_random_heads(N, b, frac, eps):
     if frac == 1.0:
         for g in res:
             assert g["pairs"] == [N * (N + 1) // 2] * 3
+
+
+def test_search_ignores_the_selection_options_of_its_context():
+    # the search's candidates are the one-top-k block rule and element-exact diagonals whatever the
+    # context it is called on was configured with
+    print("case search options", flush=True)
+    N, b, w, Hq, Hkv = 704, 64, 32, 3, 1
+    Q, K, V = gen.random_qkv(Hq, Hkv, N, 128, seed=977)
+    Qd, Kd, Vd = dev_bf16(Q), dev_bf16(K), dev_bf16(V)
+    target, eps = N * (N + 1) // 2 // 5, 300
+    out = []
+    for options in (dict(), dict(block_select=1, diagonal_select=1), dict(block_select=2)):
+        ses = sa.Session(Hq, Hkv, N, b, w, keep=0.3, **options)
+        ses.estimate(Qd, Kd)
+        torch.cuda.synchronize()
+        out.append(ses.search_patterns(Qd, Kd, Vd, target, eps))
+    v, s, blk = download_scores(ses)
+    ref = srch.search_patterns(Q, K, V, v, s, blk, b, w, ses.cfg.sink_blocks, target, eps)
+    _check(out[0], ref, N, "options")
+    for other in out[1:]:
+        for g, r in zip(other, out[0]):
+            assert g["param"] == r["param"] and g["pairs"] == r["pairs"] and g["pattern"] == r["pattern"]
