@@ -54,7 +54,7 @@ def cpu_baseline(orc, data, wl, bud, sample_rows):
 
 
 def run_workload(name, steps, warmup, layers, with_cpu, sample_rows, with_dense=False, block_select=0,
-                 diagonal_select=0, prewarm_s=PREWARM_S):
+                 diagonal_select=0, prewarm_s=PREWARM_S, lazy_block_map=0):
     import numpy as np
     import torch
 
@@ -64,7 +64,8 @@ def run_workload(name, steps, warmup, layers, with_cpu, sample_rows, with_dense=
     wl = gen.WORKLOADS[name]
     N, b, w, Hq, Hkv, d = wl.seq_len, wl.block, wl.last_q, wl.n_q_heads, wl.n_kv_heads, wl.head_dim
     dev = torch.device("cuda:0")
-    ses = sa.Session(Hq, Hkv, N, b, w, keep=wl.keep, block_select=block_select, diagonal_select=diagonal_select)
+    ses = sa.Session(Hq, Hkv, N, b, w, keep=wl.keep, block_select=block_select, diagonal_select=diagonal_select,
+                     lazy_block_map=lazy_block_map)
 
     def up(bits):
         return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(dev)
@@ -131,7 +132,7 @@ def run_workload(name, steps, warmup, layers, with_cpu, sample_rows, with_dense=
     torch.cuda.synchronize()
     wall1_ms = (time.perf_counter() - t0) * 1e3
     ph1 = np.array([[e[k].elapsed_time(e[k + 1]) for k in range(2)] for e in evs1]).mean(0)
-    log(f"[{name}] one-call form: ms/step wall {wall1_ms / steps:.3f}; estimate+index {ph1[0]:.3f} attention {ph1[1]:.3f}")
+    log(f"[{name}] one-call form{' (block map for the Block-Cluster heads only)' if lazy_block_map else ''}: ms/step wall {wall1_ms / steps:.3f}; estimate+index {ph1[0]:.3f} attention {ph1[1]:.3f}")
 
     # the three-call step recorded once per resident layer into a HIP graph and replayed
     # (a side figure: a failure here must not cost the benchmark line)
@@ -498,6 +499,8 @@ def main():
                          "fraction of every row block")
     ap.add_argument("--diagonals", choices=("exact", "blocks"), default="exact",
                     help="selected diagonals of Interval-Slash heads element-exact (default) or widened to whole blocks")
+    ap.add_argument("--lazy-block-map", action="store_true",
+                    help="one-call form: compute the block map only for the heads decided Block-Cluster")
     ap.add_argument("--block-rules", action="store_true",
                     help="compare the two block rules (time, kept pairs, error against all-keys attention) instead")
     ap.add_argument("--decode", action="store_true",
@@ -537,11 +540,13 @@ def main():
     bsel = 1 if a.block_select == "row" else 0
     dsel = 1 if a.diagonals == "blocks" else 0
     main_res = run_workload(a.workload, a.steps, a.warmup, a.layers, not a.no_cpu_baseline, a.sample_rows,
-                            block_select=bsel, diagonal_select=dsel, prewarm_s=a.prewarm)
+                            block_select=bsel, diagonal_select=dsel, prewarm_s=a.prewarm,
+                            lazy_block_map=int(a.lazy_block_map))
     also = None
     if a.also and a.also != a.workload:
         also = run_workload(a.also, max(a.steps, 20), a.warmup, min(a.layers, 2), False, a.sample_rows,
-                            with_dense=True, block_select=bsel, diagonal_select=dsel, prewarm_s=a.prewarm)
+                            with_dense=True, block_select=bsel, diagonal_select=dsel, prewarm_s=a.prewarm,
+                            lazy_block_map=int(a.lazy_block_map))
 
     traffic = None
     tp = os.path.join(ROOT, "profiles", f"traffic_{a.workload}.json")

@@ -92,6 +92,8 @@ typedef struct {
   int64_t kv_head_stride, kv_row_stride;   /* K and V; row strides must be multiples of 8 elements */
   int32_t block_select;                    /* sa_block_select; 0 => SA_BLOCKS_GLOBAL */
   int32_t diagonal_select;                 /* sa_diagonal_select; 0 => SA_DIAGONALS_EXACT */
+  int32_t lazy_block_map;                  /* 0 or 1; 1: sa_estimate_and_index computes the block map (Alg. 3) only
+                                            * for the heads that turn out Block-Cluster; see that call */
 } sa_config;
 
 /* Device score buffers written by sa_estimate_patterns (Alg. 2 SumRows /
@@ -152,7 +154,14 @@ sa_status sa_build_index(sa_ctx *ctx, sa_scores in, const int32_t *pattern_overr
  * on the caller's stream and the context's side stream: the selections on v
  * and s run while the block map is still being computed, and the block
  * selection runs beside them.  Towards the caller it behaves like a sequence
- * of kernels on `stream`.  Arguments as in the two calls; errors likewise. */
+ * of kernels on `stream`.  Arguments as in the two calls; errors likewise.
+ * With cfg.lazy_block_map = 1 the call follows the order of the categorisation
+ * instead (the blocked representation of Alg. 3 belongs to the Block-Cluster
+ * branch only): window passes, selections on v and s, pattern decision, and
+ * then block means, block map and block selection for the Block-Cluster heads
+ * alone, all on `stream`.  The index is the same, byte for byte; scores.blk of
+ * the other heads is not written (it keeps what it held), and Q is read for
+ * the Block-Cluster heads only. */
 sa_status sa_estimate_and_index(sa_ctx *ctx, const void *Q, const void *K, sa_scores scores,
                                 const int32_t *pattern_override_host, sa_index index, void *hip_stream);
 

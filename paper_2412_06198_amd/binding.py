@@ -33,7 +33,8 @@ class SaConfig(C.Structure):
                 ("lift_den", C.c_int32),
                 ("q_head_stride", C.c_int64), ("q_row_stride", C.c_int64),
                 ("kv_head_stride", C.c_int64), ("kv_row_stride", C.c_int64),
-                ("block_select", C.c_int32), ("diagonal_select", C.c_int32)]
+                ("block_select", C.c_int32), ("diagonal_select", C.c_int32),
+                ("lazy_block_map", C.c_int32)]
 
 
 class SaScores(C.Structure):

@@ -94,6 +94,7 @@ sa_status sa_create(const sa_config *cfg, sa_ctx **out) {
   if (cfg->softmax_scale < 0.f) return SA_ERR_INVALID_ARG;
   if (cfg->block_select < SA_BLOCKS_GLOBAL || cfg->block_select > SA_BLOCKS_GLOBAL_ROW_NORMALISED) return SA_ERR_INVALID_ARG;
   if (cfg->diagonal_select != SA_DIAGONALS_EXACT && cfg->diagonal_select != SA_DIAGONALS_BLOCKS) return SA_ERR_INVALID_ARG;
+  if (cfg->lazy_block_map != 0 && cfg->lazy_block_map != 1) return SA_ERR_INVALID_ARG;
 
   sa_ctx *c = new (std::nothrow) sa_ctx();
   if (!c) return SA_ERR_INVALID_ARG;
@@ -114,6 +115,7 @@ sa_status sa_create(const sa_config *cfg, sa_ctx **out) {
   const long long kcap = (long long)s.k_b + (s.row_select ? nb : 0);
   long long cap = tri > kcap ? tri : kcap;
   s.diag_blocks = cfg->diagonal_select == SA_DIAGONALS_BLOCKS;
+  s.lazy_blk = cfg->lazy_block_map;
   if (s.diag_blocks) {
     // a diagonal touches at most two key blocks per row block: row R holds min(R + 1, 2 k_s + 1)
     const long long ks = s.k_s < s.N ? s.k_s : s.N, m = 2 * ks + 1;
@@ -280,6 +282,22 @@ sa_status sa_estimate_and_index(sa_ctx *c, const void *Q, const void *K, sa_scor
   if (s != SA_OK) return s;
   hipStream_t st = (hipStream_t)stream;
   const sa::Fork &fk = c->fork;
+  if (c->sh.lazy_blk) {
+    // In the order of the categorisation, on one stream: what the Block-Cluster branch needs is
+    // computed once the heads that take it are known.
+    const uint16_t *q = (const uint16_t *)Q, *k = (const uint16_t *)K;
+    using sa::IndexStage;
+    using sa::EstimatePart;
+    hipError_t e = sa::launch_index_stage(c->sh, c->ws, scores, ov, out, IndexStage::Zero, st);
+    if (e == hipSuccess) e = sa::launch_estimate_part(c->sh, c->ws, q, k, scores, EstimatePart::KChain, nullptr, st);
+    if (e == hipSuccess) e = sa::launch_index_stage(c->sh, c->ws, scores, ov, out, IndexStage::ColumnsDiagonals, st);
+    if (e == hipSuccess) e = sa::launch_index_stage(c->sh, c->ws, scores, ov, out, IndexStage::Decide, st);
+    if (e == hipSuccess)
+      e = sa::launch_estimate_part(c->sh, c->ws, q, k, scores, EstimatePart::QChain, out.pattern, st);
+    if (e == hipSuccess) e = sa::launch_index_stage(c->sh, c->ws, scores, ov, out, IndexStage::Blocks, st, true);
+    if (e == hipSuccess) e = sa::launch_index_stage(c->sh, c->ws, scores, ov, out, IndexStage::Emit, st, true);
+    return hip_result(c, e);
+  }
   // Caller's stream: window passes -> selections on v and s; side stream: block means and block
   // map -> block selection; joined before the pattern decision and the emission.
   hipError_t e = sa::launch_index_stage(c->sh, c->ws, scores, ov, out, sa::IndexStage::Zero, st);

@@ -55,9 +55,11 @@ constexpr int kQMeanLdsPad128 = 40 * 1024, kQMeanLdsPad64 = 32 * 1024;  // by bl
 
 template <int RPT>
 __global__ __launch_bounds__(256) void q_block_mean_kernel(const uint16_t *__restrict__ Q, Shape sh,
-                                                           float *__restrict__ qblk) {
+                                                           float *__restrict__ qblk,
+                                                           const int32_t *__restrict__ only_bc) {
   __shared__ float red[16][kHeadDim + 4];
   const int R = blockIdx.x, h = blockIdx.y, tid = threadIdx.x;
+  if (only_bc && only_bc[h] != SA_BLOCK_CLUSTER) return;  // this head's block map is not wanted
   const uint16_t *src = Q + (size_t)h * sh.q_hs + (size_t)R * sh.b * sh.q_rs;
   const int cc = tid & 15, rg = tid >> 4;
   uint4 x[RPT];
@@ -476,7 +478,8 @@ template <int MT>
 __global__ __launch_bounds__(64 * kMapWaves, (MT <= 8 ? 4 : 2)) void block_map_kernel(const float *__restrict__ qblk,
                                                                    const float *__restrict__ kblk,
                                                                    Shape sh, float c2,
-                                                                   float *__restrict__ blk) {
+                                                                   float *__restrict__ blk,
+                                                                   const int32_t *__restrict__ only_bc) {
   __shared__ float red[2][kMapWaves][16];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -497,6 +500,7 @@ __global__ __launch_bounds__(64 * kMapWaves, (MT <= 8 ? 4 : 2)) void block_map_k
     strip = nstrips - 1 - L % nstrips;
     h = L / nstrips;
   }
+  if (only_bc && only_bc[h] != SA_BLOCK_CLUSTER) return;  // uniform over the workgroup, before any barrier
   const int R0 = 16 * strip;
   const int T = strip + 1;  // column tiles 0..strip hold every C <= R of this strip
   // tile t of a means array: 8 KB = [part][st][lane][16 bytes]
@@ -627,6 +631,48 @@ __global__ __launch_bounds__(64 * kMapWaves, (MT <= 8 ? 4 : 2)) void block_map_k
 
 }  // namespace
 
+namespace {
+
+void launch_q_block_mean(const Shape &sh, const Workspace &ws, const uint16_t *Q, const int32_t *only_bc,
+                         hipStream_t sq) {
+  if (sh.b == 128)
+    q_block_mean_kernel<8><<<dim3(sh.nb, sh.Hq), 256, kQMeanLdsPad128, sq>>>(Q, sh, ws.qblk, only_bc);
+  else
+    q_block_mean_kernel<4><<<dim3(sh.nb, sh.Hq), 256, kQMeanLdsPad64, sq>>>(Q, sh, ws.qblk, only_bc);
+}
+
+void launch_block_map(const Shape &sh, const Workspace &ws, float c, float *blk, const int32_t *only_bc,
+                      hipStream_t sq) {
+  const dim3 bgrid((sh.nb + 15) / 16 * sh.Hq);
+  const int tiles_per_wave = ((sh.nb + 15) / 16 + kMapWaves - 1) / kMapWaves;
+  if (tiles_per_wave <= 8)
+    block_map_kernel<8><<<bgrid, 64 * kMapWaves, 0, sq>>>(ws.qblk, ws.kblk, sh, c, blk, only_bc);
+  else if (tiles_per_wave <= 16)
+    block_map_kernel<16><<<bgrid, 64 * kMapWaves, 0, sq>>>(ws.qblk, ws.kblk, sh, c, blk, only_bc);
+  else
+    block_map_kernel<32><<<bgrid, 64 * kMapWaves, 0, sq>>>(ws.qblk, ws.kblk, sh, c, blk, only_bc);
+}
+
+}  // namespace
+
+hipError_t launch_estimate_part(const Shape &sh, const Workspace &ws, const uint16_t *Q, const uint16_t *K,
+                                sa_scores out, EstimatePart part, const int32_t *only_block_cluster,
+                                hipStream_t st) {
+  const float c = sh.scale * kLog2e;
+  float *bias = (float *)ws.stats;
+  if (part != EstimatePart::QChain) {
+    const dim3 wgrid(sh.nchunks, sh.Hkv, (sh.g + 3) / 4);
+    window_stats_kernel<<<wgrid, 256, 0, st>>>(Q, K, sh, c, ws.part, out.s, ws.kblk);
+    window_stats_reduce_kernel<<<dim3(sh.Hq, kWin / 16), 1024, 0, st>>>(ws.part, sh.nchunks, sh.w, bias);
+    window_scores_kernel<<<wgrid, 256, 0, st>>>(Q, K, sh, c, bias, out.v, out.s);
+  }
+  if (part != EstimatePart::KChain) {
+    launch_q_block_mean(sh, ws, Q, only_block_cluster, st);
+    launch_block_map(sh, ws, c, out.blk, only_block_cluster, st);
+  }
+  return hipGetLastError();
+}
+
 hipError_t launch_estimate(const Shape &sh, const Workspace &ws, const uint16_t *Q,
                            const uint16_t *K, sa_scores out, hipStream_t st, const Fork &fk,
                            bool join_back) {
@@ -646,24 +692,14 @@ hipError_t launch_estimate(const Shape &sh, const Workspace &ws, const uint16_t 
     if ((e = hipStreamWaitEvent(fk.aux, fk.fork, 0)) != hipSuccess) return e;
     sq = fk.aux;
   }
-  if (sh.b == 128)
-    q_block_mean_kernel<8><<<dim3(sh.nb, sh.Hq), 256, kQMeanLdsPad128, sq>>>(Q, sh, ws.qblk);
-  else
-    q_block_mean_kernel<4><<<dim3(sh.nb, sh.Hq), 256, kQMeanLdsPad64, sq>>>(Q, sh, ws.qblk);
+  launch_q_block_mean(sh, ws, Q, nullptr, sq);
   const dim3 wgrid(sh.nchunks, sh.Hkv, (sh.g + 3) / 4);
   window_stats_kernel<<<wgrid, 256, 0, st>>>(Q, K, sh, c, ws.part, out.s, ws.kblk);
   if (fk.aux) {  // the block map needs the K block means of the stats pass
     if ((e = hipEventRecord(fk.mid, st)) != hipSuccess) return e;
     if ((e = hipStreamWaitEvent(fk.aux, fk.mid, 0)) != hipSuccess) return e;
   }
-  const dim3 bgrid((sh.nb + 15) / 16 * sh.Hq);
-  const int tiles_per_wave = ((sh.nb + 15) / 16 + kMapWaves - 1) / kMapWaves;
-  if (tiles_per_wave <= 8)
-    block_map_kernel<8><<<bgrid, 64 * kMapWaves, 0, sq>>>(ws.qblk, ws.kblk, sh, c, out.blk);
-  else if (tiles_per_wave <= 16)
-    block_map_kernel<16><<<bgrid, 64 * kMapWaves, 0, sq>>>(ws.qblk, ws.kblk, sh, c, out.blk);
-  else
-    block_map_kernel<32><<<bgrid, 64 * kMapWaves, 0, sq>>>(ws.qblk, ws.kblk, sh, c, out.blk);
+  launch_block_map(sh, ws, c, out.blk, nullptr, sq);
   window_stats_reduce_kernel<<<dim3(sh.Hq, kWin / 16), 1024, 0, st>>>(ws.part, sh.nchunks, sh.w, bias);
   window_scores_kernel<<<wgrid, 256, 0, st>>>(Q, K, sh, c, bias, out.v, out.s);
   if (fk.aux && join_back) {

@@ -68,6 +68,9 @@ struct IdxArgs {
   int mask;
   // Heads (bit h) whose pattern override makes the v/s selections, or the block selection, unnecessary.
   uint32_t skip_vs[kMaxHeads / 32], skip_blk[kMaxHeads / 32];
+  // Not null: the patterns an earlier launch decided ([Hq], device); the block-map part of the work
+  // is then done for the Block-Cluster heads only (the block map of the others was never computed).
+  const int32_t *decided;
 };
 
 // Whether a launch has to touch one part of a head's work (the selections on v and s, or the one on
@@ -78,7 +81,8 @@ __device__ inline bool head_wants(const IdxArgs &a, int h, bool blk_part) {
   const int w = h >> 5;  // four words: selected without indexing the argument block dynamically
   const uint32_t *m = blk_part ? a.skip_blk : a.skip_vs;
   const uint32_t bits = w == 0 ? m[0] : w == 1 ? m[1] : w == 2 ? m[2] : m[3];
-  return !((bits >> (h & 31)) & 1u);
+  if ((bits >> (h & 31)) & 1u) return false;
+  return !(blk_part && a.decided) || a.decided[h] == SA_BLOCK_CLUSTER;
 }
 
 // floor(x * 2^30) of a finite fp32 x >= 0 given by its bits.
@@ -510,6 +514,13 @@ __global__ __launch_bounds__(BT) void idx_count_kernel(IdxArgs a) {
   }
 }
 
+// The pattern decision by itself, one thread per head, for a caller that needs it before the block
+// map exists (the scan launch below takes the same decision again from the same sums).
+__global__ void idx_decide_kernel(IdxArgs a) {
+  const int h = blockIdx.x * blockDim.x + threadIdx.x;
+  if (h < a.sh.Hq) a.out.pattern[h] = decide_pattern(a, a.scratch + h, h);
+}
+
 // One workgroup per head: pattern decision, prefixes of the per-part and per-row counts, rowptr.
 __global__ __launch_bounds__(BT) void idx_scan_kernel(IdxArgs a) {
   __shared__ unsigned s_wsum[2 * WPB];
@@ -828,6 +839,7 @@ IdxArgs index_args(const Shape &sh, const Workspace &ws, sa_scores in, const Ove
   a.ksel[3] = sh.k_s < sh.N ? sh.k_s : sh.N;
   a.ksel[4] = sh.row_select ? 0 : (int)kb;   // per-row rule: selected row by row while emitting
   a.mask = 3;
+  a.decided = nullptr;
   static_assert(kMaxHeads == 128, "four mask words");
   for (int w = 0; w < kMaxHeads / 32; ++w) a.skip_vs[w] = a.skip_blk[w] = 0u;
   for (int h = 0; h < sh.Hq; ++h) {
@@ -879,10 +891,12 @@ hipError_t launch_build_index(const Shape &sh, const Workspace &ws, sa_scores in
 
 // The same work in parts, so that it can run beside the estimator: the selections on v and s as
 // soon as the window passes are done, the block-map selection as soon as the block map is (on
-// another stream), and the emission once both are.
+// another stream), and the emission once both are.  Decide (after ColumnsDiagonals) writes the
+// patterns early, for a caller that computes the block map only where it is needed.
 hipError_t launch_index_stage(const Shape &sh, const Workspace &ws, sa_scores in, const Override &ov,
-                              sa_index out, IndexStage stage, hipStream_t st) {
+                              sa_index out, IndexStage stage, hipStream_t st, bool lazy) {
   IdxArgs a = index_args(sh, ws, in, ov, out);
+  if (lazy) a.decided = out.pattern;
   switch (stage) {
     case IndexStage::Zero:
       idx_zero_kernel<<<sh.Hq, 256, 0, st>>>(a.scratch);
@@ -890,6 +904,9 @@ hipError_t launch_index_stage(const Shape &sh, const Workspace &ws, sa_scores in
     case IndexStage::ColumnsDiagonals:
       a.mask = 1;
       launch_levels(a, st);
+      break;
+    case IndexStage::Decide:
+      idx_decide_kernel<<<(sh.Hq + 63) / 64, 64, 0, st>>>(a);
       break;
     case IndexStage::Blocks:
       a.mask = 2;

@@ -22,6 +22,7 @@ struct Shape {
   int row_select;                 // Block-Cluster heads: 1 = every row keeps its own share of k_b
   int row_norm;                   // Block-Cluster heads: 1 = global top-k on blk[R][C] * (R + 1)
   int diag_blocks;                // Interval-Slash heads: 1 = selected diagonals kept as whole blocks
+  int lazy_blk;                   // one-call form: 1 = block map only for the heads decided Block-Cluster
   int chunk, nchunks;             // keys per estimator workgroup (window passes), ceil(N / chunk)
   int n_cu;                       // compute units of the device the context was created on
   int64_t q_hs, q_rs, kv_hs, kv_rs;
@@ -48,7 +49,10 @@ size_t index_scratch_bytes(int n_heads);
 struct Fork { hipStream_t aux; hipEvent_t fork, mid, join; };
 
 // Parts of the index builder when it runs interleaved with the estimator.
-enum class IndexStage { Zero, ColumnsDiagonals, Blocks, Emit };
+enum class IndexStage { Zero, ColumnsDiagonals, Decide, Blocks, Emit };
+
+// Which of the estimator's two chains a call enqueues.
+enum class EstimatePart { Both, KChain, QChain };
 
 }  // namespace sa
 
@@ -69,10 +73,18 @@ namespace sa {
 hipError_t launch_estimate(const Shape &sh, const Workspace &ws, const uint16_t *Q,
                            const uint16_t *K, sa_scores out, hipStream_t st, const Fork &fk,
                            bool join_back = true);
+// One chain alone on st.  QChain needs the K block means that KChain leaves in the workspace;
+// only_block_cluster (device, [Hq] patterns, or nullptr = every head) restricts it to the heads
+// whose entry is SA_BLOCK_CLUSTER.
+hipError_t launch_estimate_part(const Shape &sh, const Workspace &ws, const uint16_t *Q, const uint16_t *K,
+                                sa_scores out, EstimatePart part, const int32_t *only_block_cluster,
+                                hipStream_t st);
 hipError_t launch_build_index(const Shape &sh, const Workspace &ws, sa_scores in,
                               const Override &ov, sa_index out, hipStream_t st);
+// lazy: the block-map part of the work is done only for the heads whose out.pattern (written by
+// the Decide stage) is SA_BLOCK_CLUSTER.
 hipError_t launch_index_stage(const Shape &sh, const Workspace &ws, sa_scores in, const Override &ov,
-                              sa_index out, IndexStage stage, hipStream_t st);
+                              sa_index out, IndexStage stage, hipStream_t st, bool lazy = false);
 size_t decode_partial_bytes(const Shape &sh);
 hipError_t launch_sparse_decode(const Shape &sh, const Workspace &ws, const uint16_t *q, const uint16_t *K,
                                 const uint16_t *V, sa_index idx, int pos, uint16_t *o, hipStream_t st);

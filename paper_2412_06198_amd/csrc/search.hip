@@ -60,6 +60,7 @@ void candidate_config(const sa_config &parent, int pattern, int64_t x, sa_config
   c->local_blocks = 1; c->k_vertical = 1; c->k_slash = 1; c->k_blocks = nb;
   c->block_select = SA_BLOCKS_GLOBAL;  // the search's Block-Cluster candidate is the one-top-k rule,
   c->diagonal_select = SA_DIAGONALS_EXACT;  // its Interval-Slash candidate the element-exact one
+  c->lazy_block_map = 0;
   if (pattern == SA_TRIANGULAR) {
     c->local_blocks = (int32_t)x;
   } else if (pattern == SA_INTERVAL_SLASH) {

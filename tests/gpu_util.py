@@ -16,12 +16,12 @@ def host_f64(t):
     return t.float().cpu().numpy().astype(np.float64)
 
 
-def make_session(Hq, Hkv, N, b, w, bud: orc.Budgets):
+def make_session(Hq, Hkv, N, b, w, bud: orc.Budgets, lazy_block_map=0):
     return sa.Session(Hq, Hkv, N, b, w, sink_blocks=bud.sink_blocks, local_blocks=bud.local_blocks,
                       k_vertical=bud.k_vertical, k_slash=bud.k_slash, k_blocks=bud.k_blocks,
                       probe_v=bud.probe_v, probe_s=bud.probe_s, lift_num=bud.lift_num,
                       lift_den=bud.lift_den, block_select=bud.block_select,
-                      diagonal_select=bud.diagonal_select)
+                      diagonal_select=bud.diagonal_select, lazy_block_map=lazy_block_map)
 
 
 def upload_index(ses, ix: orc.Index):

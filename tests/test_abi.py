@@ -53,6 +53,7 @@ def test_default_budgets_agree_with_oracle(N, b, rho):
     (dict(last_q=65), 2), (dict(seq_len=1 << 20), 2),
     (dict(n_kv_heads=5), 1), (dict(k_blocks=10), 1), (dict(local_blocks=0), 1),
     (dict(kv_row_stride=130), 2),
+    (dict(block_select=3), 1), (dict(diagonal_select=2), 1), (dict(lazy_block_map=2), 1),
 ])
 def test_create_rejects_bad_configs(kw, status):
     with pytest.raises(sa.SaError) as e:

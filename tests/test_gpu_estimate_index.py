@@ -119,3 +119,45 @@ def test_one_call_estimate_and_index_is_byte_identical(N, b, keep, rows):
         assert_index_equal(download_index(one), want)
     v, s, blk = download_scores(one)
     assert_index_equal(download_index(one), orc.build_index(v, s, blk, N, b, 64, bud))
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("N,b,keep,rows,diag", [(4096, 64, 0.10, 0, 0), (2048, 128, 0.3, 1, 0),
+                                                (8192 + 128, 128, 0.07, 2, 1), (1024, 64, 0.5, 0, 0)])
+def test_lazy_block_map_gives_the_same_index(N, b, keep, rows, diag):
+    # lazy_block_map: the block map exists for the Block-Cluster heads only; v, s and the index are
+    # those of the two calls, byte for byte, and the block map of the other heads is not written
+    print(f"case lazy N={N} b={b} rows={rows} diag={diag}", flush=True)
+    Hq, Hkv = 8, 2
+    wl = gen.scaled(gen.WORKLOADS["cfg3"], name="t", n_q_heads=Hq, n_kv_heads=Hkv, seq_len=N,
+                    block=b, seed=N + 5, n_hot=4, hot_block=b, keep=keep)
+    data = gen.generate(wl)
+    bud = orc.default_budgets(N, b, keep)
+    bud.block_select, bud.diagonal_select = rows, diag
+    Q, K = dev_bf16(data["Q"]), dev_bf16(data["K"])
+    two, lazy = make_session(Hq, Hkv, N, b, 64, bud), make_session(Hq, Hkv, N, b, 64, bud, lazy_block_map=1)
+    seen = set()
+    for ov in (None, [T, IS, BC, IS, BC, T, IS, BC], [BC] * Hq, [T] * Hq, None):
+        two.estimate(Q, K)
+        two.build_index(ov)
+        for t in lazy.index_tensors() + [lazy.v, lazy.s, lazy.blk]:
+            t.fill_(-7)
+        lazy.estimate_and_index(Q, K, ov)
+        want = download_index(two)
+        assert_index_equal(download_index(lazy), want)
+        v2, s2, blk2 = download_scores(two)
+        v1, s1, blk1 = download_scores(lazy)
+        assert v1.tobytes() == v2.tobytes() and s1.tobytes() == s2.tobytes()
+        for h in range(Hq):
+            seen.add(int(want.pattern[h]))
+            if want.pattern[h] == BC:
+                assert blk1[h].tobytes() == blk2[h].tobytes(), h
+            else:
+                assert (blk1[h] == -7).all(), h
+    assert seen == {T, IS, BC}
+    # the separate calls of a lazy context still compute every head's block map
+    lazy.blk.fill_(-7)
+    lazy.estimate(Q, K)
+    lazy.build_index(None)
+    assert download_scores(lazy)[2].tobytes() == blk2.tobytes()
+    assert_index_equal(download_index(lazy), want)

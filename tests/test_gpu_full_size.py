@@ -114,6 +114,17 @@ def test_cfg5_one_call_estimate_and_index():
             assert a.tobytes() == c.tobytes()
         assert_index_equal(download_index(one), download_index(two))
     assert len(set(download_index(one).pattern.tolist())) == 3
+    # the same with the block map computed for the Block-Cluster heads only
+    lazy = sa.Session(Hq, wl.n_kv_heads, N, b, w, keep=wl.keep, lazy_block_map=1)
+    lazy.blk.fill_(-7)
+    for rep in range(2):
+        lazy.estimate_and_index(Q, K, None)
+        want = download_index(two)
+        assert_index_equal(download_index(lazy), want)
+        assert torch.equal(lazy.v, two.v) and torch.equal(lazy.s, two.s)
+        bc = torch.from_numpy(want.pattern == 2).cuda()
+        assert torch.equal(lazy.blk[bc], two.blk[bc])
+        assert bool((lazy.blk[~bc] == -7).all())
 
 
 def test_counters_match_oracle_mask_count():
