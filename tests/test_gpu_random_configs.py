@@ -60,3 +60,7 @@ def test_random_configuration(seed):
     check_attention(host_f64(O), ref, f"random {seed}")
     tiles, kept = ses.prefill_counted(Qd, Kd, Vd, O)
     assert kept == sum(orc.mask_count(N, b, h, got) for h in range(Hq))
+    # the one-call form that computes the block map for the Block-Cluster heads only: same index
+    lz = make_session(Hq, Hkv, N, b, w, bud, lazy_block_map=1)
+    lz.estimate_and_index(Qd, Kd, ov)
+    assert_index_equal(download_index(lz), got)
