@@ -54,7 +54,7 @@ def cpu_baseline(orc, data, wl, bud, sample_rows):
 
 
 def run_workload(name, steps, warmup, layers, with_cpu, sample_rows, with_dense=False, block_select=0,
-                 diagonal_select=0, prewarm_s=PREWARM_S, lazy_block_map=0):
+                 diagonal_select=0, prewarm_s=PREWARM_S, lazy_block_map=0, force_pattern=None):
     import numpy as np
     import torch
 
@@ -64,6 +64,7 @@ def run_workload(name, steps, warmup, layers, with_cpu, sample_rows, with_dense=
     wl = gen.WORKLOADS[name]
     N, b, w, Hq, Hkv, d = wl.seq_len, wl.block, wl.last_q, wl.n_q_heads, wl.n_kv_heads, wl.head_dim
     dev = torch.device("cuda:0")
+    ov = None if force_pattern is None else [int(force_pattern)] * Hq   # every head forced to one pattern
     ses = sa.Session(Hq, Hkv, N, b, w, keep=wl.keep, block_select=block_select, diagonal_select=diagonal_select,
                      lazy_block_map=lazy_block_map)
 
@@ -86,7 +87,7 @@ def run_workload(name, steps, warmup, layers, with_cpu, sample_rows, with_dense=
         if ev: ev[0].record()
         ses.estimate(Q, K)
         if ev: ev[1].record()
-        ses.build_index(None)
+        ses.build_index(ov)
         if ev: ev[2].record()
         ses.prefill(Q, K, V, O)
         if ev: ev[3].record()
@@ -117,7 +118,7 @@ def run_workload(name, steps, warmup, layers, with_cpu, sample_rows, with_dense=
     def step1(l, ev=None):
         Q, K, V, _ = resident[l % layers]
         if ev: ev[0].record()
-        ses.estimate_and_index(Q, K, None)
+        ses.estimate_and_index(Q, K, ov)
         if ev: ev[1].record()
         ses.prefill(Q, K, V, O)
         if ev: ev[2].record()
@@ -165,7 +166,7 @@ def run_workload(name, steps, warmup, layers, with_cpu, sample_rows, with_dense=
     for l in range(layers):
         Q, K, V, planted = resident[l]
         ses.estimate(Q, K)
-        ses.build_index(None)
+        ses.build_index(ov)
         c = ses.prefill_counted(Q, K, V, O)
         tiles.append(c[0]); kept.append(c[1])
         for pp, ch in zip(planted, ses.pattern.cpu().tolist()):
@@ -499,6 +500,9 @@ def main():
                          "fraction of every row block")
     ap.add_argument("--diagonals", choices=("exact", "blocks"), default="exact",
                     help="selected diagonals of Interval-Slash heads element-exact (default) or widened to whole blocks")
+    ap.add_argument("--force-pattern", choices=["T", "IS", "BC"], default=None,
+                    help="override the pattern rule: every head Triangular, Interval-Slash or Block-Cluster "
+                         "(per-pattern timing and counters; not the benchmark's workload)")
     ap.add_argument("--lazy-block-map", action="store_true",
                     help="one-call form: compute the block map only for the heads decided Block-Cluster")
     ap.add_argument("--block-rules", action="store_true",
@@ -538,15 +542,16 @@ def main():
         run_search(a.search, not a.no_cpu_baseline)
         return
     bsel = 1 if a.block_select == "row" else 0
+    fpat = None if a.force_pattern is None else {"T": 0, "IS": 1, "BC": 2}[a.force_pattern]
     dsel = 1 if a.diagonals == "blocks" else 0
     main_res = run_workload(a.workload, a.steps, a.warmup, a.layers, not a.no_cpu_baseline, a.sample_rows,
                             block_select=bsel, diagonal_select=dsel, prewarm_s=a.prewarm,
-                            lazy_block_map=int(a.lazy_block_map))
+                            lazy_block_map=int(a.lazy_block_map), force_pattern=fpat)
     also = None
     if a.also and a.also != a.workload:
         also = run_workload(a.also, max(a.steps, 20), a.warmup, min(a.layers, 2), False, a.sample_rows,
                             with_dense=True, block_select=bsel, diagonal_select=dsel, prewarm_s=a.prewarm,
-                            lazy_block_map=int(a.lazy_block_map))
+                            lazy_block_map=int(a.lazy_block_map), force_pattern=fpat)
 
     traffic = None
     tp = os.path.join(ROOT, "profiles", f"traffic_{a.workload}.json")
@@ -563,7 +568,8 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{a.workload}: Hq={wl.n_q_heads} Hkv={wl.n_kv_heads} d={wl.head_dim} "
                                f"N={wl.seq_len} block={wl.block} last_q={wl.last_q} keep={wl.keep} "
-                               f"layers={a.layers} (seeds {wl.seed}..{wl.seed + a.layers - 1}), patterns chosen at run time"
+                               f"layers={a.layers} (seeds {wl.seed}..{wl.seed + a.layers - 1}), "
+                               + ("patterns chosen at run time" if fpat is None else f"every head forced to pattern {a.force_pattern}")
                                + (", blocks chosen per row" if bsel else "")
                                + (", diagonals widened to blocks" if dsel else "")},
         "roofline": {"bound": "mfma", "kernel": "sparse_prefill_kernel",
