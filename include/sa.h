@@ -168,7 +168,9 @@ sa_status sa_estimate_and_index(sa_ctx *ctx, const void *Q, const void *K, sa_sc
 /* Alg. 2 / Alg. 3 "Compute Sparse Attention": O[h][i] = sum over the kept
  * keys j of softmax_j(scale * Q_h[i].K[j]) V[j].  Q, O [Hq][N][d]; K, V
  * [Hkv][N][d] bf16 device.  Any index in the documented layout is accepted,
- * not only one produced by sa_build_index. */
+ * not only one produced by sa_build_index; a query that keeps no key (its row
+ * block lists no block that reaches it, and no column or offset applies) gets
+ * a row of zeros. */
 sa_status sa_sparse_prefill(sa_ctx *ctx, const void *Q, const void *K, const void *V,
                             sa_index idx, void *O, void *hip_stream);
 

@@ -88,3 +88,58 @@ def test_planted_cfg1_shape_full_rows():
     check_attention(O, ref, "cfg1")
     O2 = _run(ses, data["Q"], data["K"], data["V"])
     assert (O == O2).all()                      # deterministic run to run
+
+
+def _random_index(rng, Hq, N, b, k_v, k_s, cap):
+    nb = N // b
+    pattern = rng.integers(0, 3, Hq).astype(np.int32)
+    n_cols = np.zeros(Hq, np.int32); cols = np.full((Hq, k_v), -1, np.int32)
+    n_offs = np.zeros(Hq, np.int32); offs = np.full((Hq, k_s), -1, np.int32)
+    rowptr = np.zeros((Hq, nb + 1), np.int32); blkcols = np.full((Hq, cap), -1, np.int32)
+    for h in range(Hq):
+        mode = rng.integers(0, 6)
+        pb = [0.0, 0.05, 0.2, 0.5, 0.9, 0.3][mode]
+        pdiag = [0.0, 1.0, 0.8, 0.5, 1.0, 0.0][mode]
+        pos = 0
+        for R in range(nb):
+            cs = [C for C in range(R) if rng.random() < pb]
+            if rng.random() < pdiag: cs.append(R)
+            if rng.random() < 0.1 and R + 1 < nb: cs.append(int(rng.integers(R + 1, nb)))  # above the diagonal: holds no visible key
+            rowptr[h, R] = pos
+            blkcols[h, pos:pos + len(cs)] = cs
+            pos += len(cs)
+        rowptr[h, nb] = pos
+        if rng.random() < 0.7:
+            n = int(rng.integers(0, k_v + 1)); n_cols[h] = n
+            cols[h, :n] = np.sort(rng.choice(N, n, replace=False))
+        if rng.random() < 0.7:
+            n = int(rng.integers(0, k_s + 1)); n_offs[h] = n
+            o = np.sort(rng.choice(N, n, replace=False))
+            if n and rng.random() < 0.5: o[0] = 0
+            offs[h, :n] = np.unique(o)[:n] if len(np.unique(o)) == n else o
+    return orc.Index(pattern, n_cols, cols, n_offs, offs, rowptr, blkcols)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_hand_made_indices(seed):
+    # any index in the documented layout is accepted, not only what sa_build_index writes: rows
+    # without their diagonal block, rows and heads that keep nothing (output 0), blocks above the
+    # diagonal, columns and offsets beside arbitrary block sets
+    rng = np.random.default_rng(50000 + seed)
+    b = int(rng.choice([64, 128])); nb = int(rng.integers(1, 13)); N = nb * b
+    Hkv = int(rng.choice([1, 2, 3])); g = int(rng.choice([1, 2, 4])); Hq = Hkv * g
+    k_v = int(rng.integers(1, min(N, 200) + 1)); k_s = int(rng.integers(1, min(N, 24) + 1))
+    bud = orc.Budgets(1, 1, k_v, k_s, nb * (nb + 1) // 2 + nb)
+    print(f"case hand-made index seed={seed} Hq={Hq} Hkv={Hkv} N={N} b={b} k_v={k_v} k_s={k_s}", flush=True)
+    Q, K, V = gen.random_qkv(Hq, Hkv, N, 128, seed=seed)
+    ses = make_session(Hq, Hkv, N, b, min(64, N), bud)
+    ix = _random_index(rng, Hq, N, b, k_v, k_s, ses.cap_b)
+    upload_index(ses, ix)
+    Qd, Kd, Vd = dev_bf16(Q), dev_bf16(K), dev_bf16(V)
+    O = torch.empty_like(Qd)
+    ses.prefill(Qd, Kd, Vd, O)
+    torch.cuda.synchronize()
+    ref, ws, kept = orc.masked_rows(Q, K, V, b, ix)
+    check_attention(host_f64(O), ref, f"index fuzz {seed}")
+    tiles, kp = ses.prefill_counted(Qd, Kd, Vd, O)
+    assert kp == int(kept.sum()), (kp, int(kept.sum()))
