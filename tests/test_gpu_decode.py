@@ -8,7 +8,7 @@ import paper_2412_06198_amd as sa
 from harness import gen
 from oracle import oracle as orc
 from oracle import decode as dec
-from gpu_util import dev_bf16, download_index, host_f64
+from gpu_util import dev_bf16, download_index, host_f64, random_index, upload_index
 
 pytestmark = pytest.mark.gpu
 
@@ -91,3 +91,30 @@ def test_decode_empty_index_parts_and_argument_checks():
     assert np.abs(host_f64(o) - ref).max() <= 2e-2
     with pytest.raises(sa.SaError):
         ses.decode(q, Kd, Vd, N - 1, o)          # a position inside the prompt is not a decode step
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_decode_over_hand_made_indices(seed):
+    # the decode step reads the same lists as the prefill: arbitrary block sets of the last row block
+    # (also none), arbitrary columns and offsets
+    rng = np.random.default_rng(70000 + seed)
+    b = int(rng.choice([64, 128])); nb = int(rng.integers(1, 13)); N = nb * b
+    Hkv = int(rng.choice([1, 2, 3])); g = int(rng.choice([1, 2, 4])); Hq = Hkv * g
+    k_v = int(rng.integers(1, min(N, 200) + 1)); k_s = int(rng.integers(1, min(N, 24) + 1))
+    extra = int(rng.integers(1, 40))
+    print(f"case decode hand-made index seed={seed} Hq={Hq} Hkv={Hkv} N={N} b={b} k_v={k_v} k_s={k_s} extra={extra}", flush=True)
+    Q, K, V = gen.random_qkv(Hq, Hkv, N + extra, 128, seed=seed)
+    ses = sa.Session(Hq, Hkv, N, b, min(64, N), sink_blocks=1, local_blocks=1, k_vertical=k_v, k_slash=k_s,
+                     k_blocks=nb * (nb + 1) // 2 + nb, q_head_stride=(N + extra) * 128,
+                     kv_head_stride=(N + extra) * 128)
+    ix = random_index(rng, Hq, N, b, k_v, k_s, ses.cap_b)
+    upload_index(ses, ix)
+    Qd, Kd, Vd = dev_bf16(Q), dev_bf16(K), dev_bf16(V)
+    for pos in sorted({N, N + extra - 1, N + int(rng.integers(0, extra))}):
+        q = Qd[:, pos].contiguous()
+        o = torch.full_like(q, 7.0)
+        ses.decode(q, Kd, Vd, pos, o)
+        torch.cuda.synchronize()
+        ref, cnt = dec.decode_step(Q[:, pos], K, V, b, ix, N, pos)
+        err = np.abs(host_f64(o) - ref)
+        assert err.max() <= 2e-2 and err.mean() <= 2e-3, (pos, float(err.max()), float(err.mean()))

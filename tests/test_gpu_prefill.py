@@ -7,7 +7,7 @@ import torch
 
 from harness import gen
 from oracle import oracle as orc
-from gpu_util import (check_attention, dev_bf16, host_f64, make_session, upload_index)
+from gpu_util import (check_attention, dev_bf16, host_f64, make_session, random_index, upload_index)
 
 pytestmark = pytest.mark.gpu
 T, IS, BC = 0, 1, 2
@@ -90,36 +90,6 @@ def test_planted_cfg1_shape_full_rows():
     assert (O == O2).all()                      # deterministic run to run
 
 
-def _random_index(rng, Hq, N, b, k_v, k_s, cap):
-    nb = N // b
-    pattern = rng.integers(0, 3, Hq).astype(np.int32)
-    n_cols = np.zeros(Hq, np.int32); cols = np.full((Hq, k_v), -1, np.int32)
-    n_offs = np.zeros(Hq, np.int32); offs = np.full((Hq, k_s), -1, np.int32)
-    rowptr = np.zeros((Hq, nb + 1), np.int32); blkcols = np.full((Hq, cap), -1, np.int32)
-    for h in range(Hq):
-        mode = rng.integers(0, 6)
-        pb = [0.0, 0.05, 0.2, 0.5, 0.9, 0.3][mode]
-        pdiag = [0.0, 1.0, 0.8, 0.5, 1.0, 0.0][mode]
-        pos = 0
-        for R in range(nb):
-            cs = [C for C in range(R) if rng.random() < pb]
-            if rng.random() < pdiag: cs.append(R)
-            if rng.random() < 0.1 and R + 1 < nb: cs.append(int(rng.integers(R + 1, nb)))  # above the diagonal: holds no visible key
-            rowptr[h, R] = pos
-            blkcols[h, pos:pos + len(cs)] = cs
-            pos += len(cs)
-        rowptr[h, nb] = pos
-        if rng.random() < 0.7:
-            n = int(rng.integers(0, k_v + 1)); n_cols[h] = n
-            cols[h, :n] = np.sort(rng.choice(N, n, replace=False))
-        if rng.random() < 0.7:
-            n = int(rng.integers(0, k_s + 1)); n_offs[h] = n
-            o = np.sort(rng.choice(N, n, replace=False))
-            if n and rng.random() < 0.5: o[0] = 0
-            offs[h, :n] = np.unique(o)[:n] if len(np.unique(o)) == n else o
-    return orc.Index(pattern, n_cols, cols, n_offs, offs, rowptr, blkcols)
-
-
 @pytest.mark.parametrize("seed", range(16))
 def test_hand_made_indices(seed):
     # any index in the documented layout is accepted, not only what sa_build_index writes: rows
@@ -133,7 +103,7 @@ def test_hand_made_indices(seed):
     print(f"case hand-made index seed={seed} Hq={Hq} Hkv={Hkv} N={N} b={b} k_v={k_v} k_s={k_s}", flush=True)
     Q, K, V = gen.random_qkv(Hq, Hkv, N, 128, seed=seed)
     ses = make_session(Hq, Hkv, N, b, min(64, N), bud)
-    ix = _random_index(rng, Hq, N, b, k_v, k_s, ses.cap_b)
+    ix = random_index(rng, Hq, N, b, k_v, k_s, ses.cap_b)
     upload_index(ses, ix)
     Qd, Kd, Vd = dev_bf16(Q), dev_bf16(K), dev_bf16(V)
     O = torch.empty_like(Qd)
