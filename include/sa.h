@@ -144,7 +144,10 @@ sa_status sa_estimate_patterns(sa_ctx *ctx, const void *Q, const void *K, sa_sco
  * Alg. 2 TopK / CombineIndices, Alg. 3 TopKBlocks.  Integer-exact: scores are
  * compared by their fp32 bit patterns, ties go to the lower index.
  * pattern_override_host: HOST array of n_q_heads sa_pattern values
- * (SA_PATTERN_AUTO = decide), or NULL for all-auto.  Writes all of `out`. */
+ * (SA_PATTERN_AUTO = decide), or NULL for all-auto.  Writes all of `out`.
+ * The scores must be what sa_estimate_patterns writes: finite and >= +0 (sign
+ * bit clear).  Other values are selected among in an unspecified order; no
+ * access leaves the buffers. */
 sa_status sa_build_index(sa_ctx *ctx, sa_scores in, const int32_t *pattern_override_host,
                          sa_index out, void *hip_stream);
 
