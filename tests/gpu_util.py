@@ -4,6 +4,7 @@ import torch
 
 import paper_2412_06198_amd as sa
 from oracle import oracle as orc
+from helpers import random_index  # noqa: F401  (used by the GPU tests through this module)
 
 MAX_ABS, MEAN_ABS = 2e-2, 2e-3        # attention output tolerance against the fp64 oracle
 
@@ -59,36 +60,3 @@ def assert_index_equal(a: orc.Index, b: orc.Index, heads=None):
         if heads is not None:
             x, y = x[heads], y[heads]
         assert x.tobytes() == y.tobytes(), f"index array {n} differs"
-
-
-def random_index(rng, Hq, N, b, k_v, k_s, cap) -> orc.Index:
-    """A hand-made index in the documented layout that no pattern produces: per head an arbitrary
-    block set per row (with or without the diagonal block, possibly nothing at all, now and then a
-    block above the diagonal), and arbitrary columns and offsets."""
-    nb = N // b
-    pattern = rng.integers(0, 3, Hq).astype(np.int32)
-    n_cols = np.zeros(Hq, np.int32); cols = np.full((Hq, k_v), -1, np.int32)
-    n_offs = np.zeros(Hq, np.int32); offs = np.full((Hq, k_s), -1, np.int32)
-    rowptr = np.zeros((Hq, nb + 1), np.int32); blkcols = np.full((Hq, cap), -1, np.int32)
-    for h in range(Hq):
-        mode = rng.integers(0, 6)
-        pb = [0.0, 0.05, 0.2, 0.5, 0.9, 0.3][mode]
-        pdiag = [0.0, 1.0, 0.8, 0.5, 1.0, 0.0][mode]
-        pos = 0
-        for R in range(nb):
-            cs = [C for C in range(R) if rng.random() < pb]
-            if rng.random() < pdiag: cs.append(R)
-            if rng.random() < 0.1 and R + 1 < nb: cs.append(int(rng.integers(R + 1, nb)))  # above the diagonal: holds no visible key
-            rowptr[h, R] = pos
-            blkcols[h, pos:pos + len(cs)] = cs
-            pos += len(cs)
-        rowptr[h, nb] = pos
-        if rng.random() < 0.7:
-            n = int(rng.integers(0, k_v + 1)); n_cols[h] = n
-            cols[h, :n] = np.sort(rng.choice(N, n, replace=False))
-        if rng.random() < 0.7:
-            n = int(rng.integers(0, k_s + 1)); n_offs[h] = n
-            o = np.sort(rng.choice(N, n, replace=False))
-            if n and rng.random() < 0.5: o[0] = 0
-            offs[h, :n] = np.unique(o)[:n] if len(np.unique(o)) == n else o
-    return orc.Index(pattern, n_cols, cols, n_offs, offs, rowptr, blkcols)

@@ -4,7 +4,7 @@ import pytest
 
 from harness import gen
 from oracle import oracle as orc
-from helpers import numpy_mask, torch_attention
+from helpers import numpy_mask, random_index, torch_attention
 
 T, IS, BC = 0, 1, 2
 
@@ -80,3 +80,28 @@ def test_union_counts_a_key_once():
     assert kb[0, 50] == 19 + 1 + 1
     mask = numpy_mask(N, b, idx([5], [40]), 0)[None]
     assert np.abs(base - torch_attention(Q, K, V, mask=mask)).max() <= 1e-12
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_hand_made_indices_and_rows_that_keep_nothing(seed):
+    # indices no pattern produces (rows without their diagonal block, empty rows and heads, blocks
+    # above the diagonal): the oracle against library attention under an independently built mask;
+    # a row that keeps no key is a row of zeros with weight sum 0
+    rng = np.random.default_rng(90000 + seed)
+    Hq, Hkv, N, b = 4, 2, 256, 32
+    nb = N // b
+    Q, K, V = gen.random_qkv(Hq, Hkv, N, 128, seed=seed)
+    ix = random_index(rng, Hq, N, b, 20, 6, nb * (nb + 1) // 2 + nb)
+    O, ws, kept = orc.masked_rows(Q, K, V, b, ix)
+    mask = np.stack([numpy_mask(N, b, ix, h) for h in range(Hq)])
+    assert (kept == mask.sum(2)).all()
+    empty = kept == 0
+    assert empty.any() and (~empty).any()
+    safe = mask.copy()
+    safe[empty, 0] = True                     # the library has no convention for an empty row
+    ref = torch_attention(Q, K, V, mask=safe)
+    assert np.abs(O[~empty] - ref[~empty]).max() <= 1e-12
+    assert np.abs(ws[~empty] - 1).max() <= 1e-12
+    assert (O[empty] == 0).all() and (ws[empty] == 0).all()
+    for h in range(Hq):
+        assert orc.mask_count(N, b, h, ix) == mask[h].sum()
