@@ -484,15 +484,18 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
     }
     const float m_ref = (m_run == -INFINITY) ? 0.f : m_run;
     float psum = 0.f;
+    // Probabilities of key step g (8 of this lane's 32 entries, the B operand of that step's four
+    // MFMAs).  Step g + 1 is computed between the MFMAs of step g: vector-ALU and matrix
+    // instructions of one wave overlap only when they alternate in its instruction stream.
+    auto soft8 = [&](int g) {
 #pragma unroll
-    for (int hf = 0; hf < 2; ++hf)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[hf][r], p.c, -m_ref));
-        sacc[hf][r] = pe;
+      for (int e = 0; e < 8; ++e) {
+        const float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[g >> 1][8 * (g & 1) + e], p.c, -m_ref));
+        sacc[g >> 1][8 * (g & 1) + e] = pe;
         psum += pe;
       }
-    l_run += psum;
+    };
+    soft8(0);
     // ---- O^T += V^T P^T : k-slot (gg,e) of step (hf,u) <-> key 32hf + 16u + 8(e/4) + 4gg + e%4 ----
     __builtin_amdgcn_s_setprio(1);
     const uint16_t *Vt = Vs[cur];
@@ -511,6 +514,7 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
         if (db == 0) {
 #pragma unroll
           for (int e = 0; e < 8; ++e) pb[e] = (__bf16)sacc[g >> 1][8 * (g & 1) + e];
+          if (g + 1 < 4) soft8(g + 1);
         }
         const s16x8 av = __builtin_shufflevector(vlo[i & 3], vhi[i & 3], 0, 1, 2, 3, 4, 5, 6, 7);
         oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pb, oacc[db], 0, 0, 0);
@@ -519,14 +523,20 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
           vhi[i & 3] = SA_VTR(Vt, (i + 4) & 3, 16 * ((i + 4) >> 2) + 8);
         }
       }
+      // order: the first step's probabilities and eight LDS reads; then per MFMA of the steps 0..2
+      // two LDS reads and a share of the next step's exp / add / convert work; then the last four
+      __builtin_amdgcn_sched_group_barrier(0x002, 24, 1);
       __builtin_amdgcn_sched_group_barrier(0x100, 8, 1);
+      __builtin_amdgcn_sched_group_barrier(0x002, 4, 1);
 #pragma unroll
       for (int i = 0; i < 12; ++i) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
         __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
+        __builtin_amdgcn_sched_group_barrier(0x002, 7, 1);
       }
       __builtin_amdgcn_sched_group_barrier(0x008, 4, 1);
     }
+    l_run += psum;
   }
 
   // ---- selected diagonals: one 32-key tile per (wave, offset), no workgroup barriers -----------
