@@ -41,6 +41,7 @@ void carve(sa_ctx *c) {
   c->off[8] = o; o += align256(sa::index_scratch_bytes(s.Hq));
   c->off[9] = o; o += align256((size_t)s.Hq * (s.N / 32) * 4);
   c->off[10] = o; o += align256(sa::decode_partial_bytes(s));
+  c->off[11] = o; o += align256((size_t)(s.Hq + s.Hkv) * 4);
   c->ws_bytes = o;
 }
 
@@ -226,6 +227,7 @@ sa_status sa_set_workspace(sa_ctx *c, void *dev, size_t bytes) {
   c->ws.idx = (void *)(p + c->off[8]);
   c->ws.colprefix = (int32_t *)(p + c->off[9]);
   c->ws.dec_part = (float *)(p + c->off[10]);
+  c->ws.hperm = (int32_t *)(p + c->off[11]);
   c->have_ws = true;
   return SA_OK;
 }

@@ -44,6 +44,9 @@ struct AttnArgs {
   int xs;       // queues (XCDs) that share one KV head at a time: 1, 2, 4 or 8
   int qcap;     // tickets per queue, holes of the id space included
   unsigned long long *counters;  // instrumentation only: {32x32 sub-tiles multiplied, kept (query,key) pairs}
+  // Per KV head, written by index_prepare_kernel: [0] = number c of its query heads without
+  // selected diagonals, [1..g] = the query heads of the group (0..g-1), those c first.
+  int32_t *hperm;
 };
 
 // Read-only words at a wave-uniform address: through the constant address space these become
@@ -73,6 +76,15 @@ __global__ __launch_bounds__(256) void index_prepare_kernel(AttnArgs p, unsigned
   if ((int)blockIdx.x < p.Hq) {
     const int h = blockIdx.x, nw = p.N / 32, lane = tid & 63, wv = tid >> 6;
     if (h == 0 && tid < 8) queue[tid] = 0u;
+    if (h < p.Hkv && tid == 0) {  // the order in which the attention kernel walks the heads of KV head h
+      int32_t *pm = p.hperm + (size_t)h * (p.g + 1);
+      int c = 0;
+      for (int j = 0; j < p.g; ++j)
+        if (p.n_offs[h * p.g + j] <= 0) pm[1 + c++] = j;
+      pm[0] = c;
+      for (int j = 0; j < p.g; ++j)
+        if (p.n_offs[h * p.g + j] > 0) pm[1 + c++] = j;
+    }
     for (int i = tid; i < nw; i += 256) bm[i] = 0u;
     __syncthreads();
     const int nc = min(max(p.n_cols[h], 0), p.k_v);
@@ -145,7 +157,9 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
   // larger xs fewer KV heads are live at once, so that the rows the diagonal phase fetches (no
   // reuse inside an L2) come out of the memory-side cache instead of HBM.  Ticket k of queue qn:
   // phase k / per_q selects the KV head, the rest walks the row blocks qn % xs, qn % xs + xs, ...
-  // from the last (longest) one down, the g query heads of a row block side by side.  A
+  // from the last (longest) one down: first for the query heads of the group that have no
+  // selected diagonals, side by side per row block, then for each head with diagonals by itself
+  // (the order index_prepare_kernel left in hperm).  A
   // workgroup whose own queue is empty takes from the others, then exits.  The ticket for the
   // next item of the home queue is drawn while the current item finishes, so its round trip is
   // off the critical path.
@@ -187,10 +201,24 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
     const int nslots = 8 / p.xs, slot = qn / p.xs, sub = qn % p.xs;
     const int per_q = (p.nT + p.xs - 1) / p.xs * p.g;
     const int r = k % per_q;
-    const int tidx = r / p.g * p.xs + sub;
     kvh = k / per_q * nslots + slot;
-    if (kvh >= p.Hkv || tidx >= p.nT) continue;  // a hole of the id space
-    h = kvh * p.g + r % p.g;
+    if (kvh >= p.Hkv) continue;  // a hole of the id space
+    // Heads without selected diagonals walk a row block side by side (their tiles overlap: the
+    // band of Triangular heads is the same for all of them); heads with diagonals follow one at a
+    // time (their diagonal phase re-reads nothing, and one head's gathered columns stay in L2).
+    const int rows_q = per_q / p.g;
+    const int32_t *pm = p.hperm + (size_t)kvh * (p.g + 1);
+    const int c = min(max((int)uload(pm, 0), 0), p.g);
+    int slot_h, trow;
+    if (r < c * rows_q) {
+      slot_h = r % c; trow = r / c;
+    } else {
+      const int r2 = r - c * rows_q;
+      slot_h = c + r2 / rows_q; trow = r2 % rows_q;
+    }
+    const int tidx = trow * p.xs + sub;
+    if (tidx >= p.nT) continue;  // a hole of the id space
+    h = kvh * p.g + min(max((int)uload(pm, 1 + slot_h), 0), p.g - 1);
     t128 = p.nT - 1 - tidx;
   }
   const int i0 = t128 * BQ;
@@ -751,6 +779,7 @@ hipError_t launch_sparse_prefill(const Shape &sh, const Workspace &ws, const uin
   a.q_hs = sh.q_hs; a.q_rs = sh.q_rs; a.kv_hs = sh.kv_hs; a.kv_rs = sh.kv_rs;
   a.c = sh.scale * 1.4426950408889634f;
   a.counters = counters;
+  a.hperm = ws.hperm;
   a.Kg = ws.kg; a.Vg = ws.vg; a.kvg_rows = (sh.k_v + BK - 1) / BK * BK;
   index_prepare_kernel<<<sh.Hq + a.kvg_rows / BK * sh.Hq, 256, 0, st>>>(a, ws.queue);
   hipError_t e = hipGetLastError();

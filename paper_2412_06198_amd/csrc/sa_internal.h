@@ -39,6 +39,7 @@ struct Workspace {
   unsigned int *queue;            // [8] work-queue heads of the attention kernel
   void *idx;                      // per-head scratch of the index builder
   uint16_t *kg, *vg;              // [Hq][roundup64(k_v)][kv_rs] gathered K / V rows of the selected columns
+  int32_t *hperm;                 // [Hkv][g + 1] order of a KV head's query heads in the attention kernel's queues
 };
 
 size_t index_scratch_bytes(int n_heads);
@@ -64,7 +65,7 @@ struct sa_ctx {
   sa::Fork fork;
   bool have_ws;
   size_t ws_bytes;
-  size_t off[11];
+  size_t off[12];
   char err[256];
 };
 
