@@ -150,17 +150,23 @@ def sa_estimate_patterns(ctx, Q, K, scores: SaScores, stream=None):
     _check(library().sa_estimate_patterns(ctx, _ptr(Q), _ptr(K), scores, stream), ctx)
 
 
-def sa_build_index(ctx, scores: SaScores, pattern_override, index: SaIndex, stream=None):
-    ov = None
-    if pattern_override is not None:
-        ov = (C.c_int32 * len(pattern_override))(*[int(p) for p in pattern_override])
+def _override_array(pattern_override, n_q_heads):
+    """Host int32 array of exactly n_q_heads entries (the library reads that many), or None."""
+    if pattern_override is None:
+        return None
+    if n_q_heads is None or len(pattern_override) != n_q_heads:
+        raise SaError(1, f"pattern_override needs one entry per query head ({n_q_heads}), got {len(pattern_override)}")
+    return (C.c_int32 * n_q_heads)(*[int(p) for p in pattern_override])
+
+
+def sa_build_index(ctx, scores: SaScores, pattern_override, index: SaIndex, stream=None, n_q_heads=None):
+    ov = _override_array(pattern_override, n_q_heads)
     _check(library().sa_build_index(ctx, scores, ov, index, stream), ctx)
 
 
-def sa_estimate_and_index(ctx, Q, K, scores: SaScores, pattern_override, index: SaIndex, stream=None):
-    ov = None
-    if pattern_override is not None:
-        ov = (C.c_int32 * len(pattern_override))(*[int(p) for p in pattern_override])
+def sa_estimate_and_index(ctx, Q, K, scores: SaScores, pattern_override, index: SaIndex, stream=None,
+                          n_q_heads=None):
+    ov = _override_array(pattern_override, n_q_heads)
     _check(library().sa_estimate_and_index(ctx, _ptr(Q), _ptr(K), scores, ov, index, stream), ctx)
 
 
@@ -255,10 +261,12 @@ class Session:
         sa_estimate_patterns(self.ctx, Q, K, self.scores(), self.stream())
 
     def build_index(self, pattern_override=None):
-        sa_build_index(self.ctx, self.scores(), pattern_override, self.index(), self.stream())
+        sa_build_index(self.ctx, self.scores(), pattern_override, self.index(), self.stream(),
+                       n_q_heads=self.cfg.n_q_heads)
 
     def estimate_and_index(self, Q, K, pattern_override=None):
-        sa_estimate_and_index(self.ctx, Q, K, self.scores(), pattern_override, self.index(), self.stream())
+        sa_estimate_and_index(self.ctx, Q, K, self.scores(), pattern_override, self.index(), self.stream(),
+                              n_q_heads=self.cfg.n_q_heads)
 
     def prefill(self, Q, K, V, O):
         sa_sparse_prefill(self.ctx, Q, K, V, self.index(), O, self.stream())

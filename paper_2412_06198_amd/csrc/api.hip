@@ -270,6 +270,7 @@ sa_status sa_build_index(sa_ctx *c, sa_scores in, const int32_t *override_host, 
   sa::Override ov;
   const sa_status s = check_index_args(c, in, override_host, out, &ov);
   if (s != SA_OK) return s;
+  if (!c->have_ws) return fail(c, SA_ERR_INVALID_ARG, "no workspace attached");
   return hip_result(c, sa::launch_build_index(c->sh, c->ws, in, ov, out, (hipStream_t)stream));
 }
 
@@ -355,6 +356,10 @@ sa_status sa_sparse_decode(sa_ctx *c, const void *q, const void *K, const void *
     return fail(c, SA_ERR_INVALID_ARG, "q, K, V must be 16-byte aligned");
   if (pos < c->sh.N || pos - c->sh.N >= (1 << 20))
     return fail(c, SA_ERR_INVALID_ARG, "pos must lie in [seq_len, seq_len + 2^20)");
+  // rows 0..pos of a KV head must fit inside its own stride, or they would alias the next head's
+  // rows (and leave the buffer behind the last head)
+  if ((pos + 1) * c->sh.kv_rs > c->sh.kv_hs)
+    return fail(c, SA_ERR_INVALID_ARG, "kv_head_stride leaves no room for key rows up to pos");
   if (!c->have_ws) return fail(c, SA_ERR_INVALID_ARG, "no workspace attached");
   return hip_result(c, sa::launch_sparse_decode(c->sh, c->ws, (const uint16_t *)q, (const uint16_t *)K,
                                                 (const uint16_t *)V, idx, (int)pos, (uint16_t *)o,

@@ -686,26 +686,34 @@ hipError_t launch_estimate(const Shape &sh, const Workspace &ws, const uint16_t 
   // (join_back == false: the caller of this function goes on using both streams and joins them
   // itself).
   hipStream_t sq = st;
-  hipError_t e;
+  hipError_t e = hipSuccess;
+  bool forked = false;
   if (fk.aux) {
     if ((e = hipEventRecord(fk.fork, st)) != hipSuccess) return e;
     if ((e = hipStreamWaitEvent(fk.aux, fk.fork, 0)) != hipSuccess) return e;
     sq = fk.aux;
+    forked = true;
   }
+  // From here on the side stream depends on the caller's stream: whatever fails below, it is joined
+  // back before the call returns, so that no later call (or an active capture) sees it dangling.
   launch_q_block_mean(sh, ws, Q, nullptr, sq);
   const dim3 wgrid(sh.nchunks, sh.Hkv, (sh.g + 3) / 4);
   window_stats_kernel<<<wgrid, 256, 0, st>>>(Q, K, sh, c, ws.part, out.s, ws.kblk);
-  if (fk.aux) {  // the block map needs the K block means of the stats pass
-    if ((e = hipEventRecord(fk.mid, st)) != hipSuccess) return e;
-    if ((e = hipStreamWaitEvent(fk.aux, fk.mid, 0)) != hipSuccess) return e;
+  if (forked) {  // the block map needs the K block means of the stats pass
+    e = hipEventRecord(fk.mid, st);
+    if (e == hipSuccess) e = hipStreamWaitEvent(fk.aux, fk.mid, 0);
   }
-  launch_block_map(sh, ws, c, out.blk, nullptr, sq);
-  window_stats_reduce_kernel<<<dim3(sh.Hq, kWin / 16), 1024, 0, st>>>(ws.part, sh.nchunks, sh.w, bias);
-  window_scores_kernel<<<wgrid, 256, 0, st>>>(Q, K, sh, c, bias, out.v, out.s);
-  if (fk.aux && join_back) {
-    if ((e = hipEventRecord(fk.join, fk.aux)) != hipSuccess) return e;
-    if ((e = hipStreamWaitEvent(st, fk.join, 0)) != hipSuccess) return e;
+  if (e == hipSuccess) {
+    launch_block_map(sh, ws, c, out.blk, nullptr, sq);
+    window_stats_reduce_kernel<<<dim3(sh.Hq, kWin / 16), 1024, 0, st>>>(ws.part, sh.nchunks, sh.w, bias);
+    window_scores_kernel<<<wgrid, 256, 0, st>>>(Q, K, sh, c, bias, out.v, out.s);
   }
+  if (forked && (join_back || e != hipSuccess)) {
+    hipError_t j = hipEventRecord(fk.join, fk.aux);
+    if (j == hipSuccess) j = hipStreamWaitEvent(st, fk.join, 0);
+    if (e == hipSuccess) e = j;
+  }
+  if (e != hipSuccess) return e;
   return hipGetLastError();
 }
 

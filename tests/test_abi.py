@@ -77,6 +77,44 @@ def test_compute_calls_validate_before_launching():
     assert e.value.status == 3
     ix = sa.SaIndex(*([256] * 7))
     with pytest.raises(sa.SaError) as e:
-        sa.sa_build_index(ctx, sa.SaScores(256, 256, 256), [7] * 32, ix, None)
+        sa.sa_build_index(ctx, sa.SaScores(256, 256, 256), [7] * 32, ix, None, n_q_heads=32)
     assert "override" in str(e.value)
+    # the binding refuses an override list that is not one entry per query head (the library
+    # reads n_q_heads entries from the host array)
+    with pytest.raises(sa.SaError) as e:
+        sa.sa_build_index(ctx, sa.SaScores(256, 256, 256), [0] * 31, ix, None, n_q_heads=32)
+    assert "per query head" in str(e.value)
+    # valid arguments but no workspace: every compute call stops before its first launch
+    with pytest.raises(sa.SaError) as e:
+        sa.sa_build_index(ctx, sa.SaScores(256, 256, 256), None, ix, None)
+    assert e.value.status == 1 and "workspace" in str(e.value)
+    with pytest.raises(sa.SaError) as e:
+        sa.sa_estimate_and_index(ctx, 256, 256, sa.SaScores(256, 256, 256), None, ix, None)
+    assert "workspace" in str(e.value)
+    with pytest.raises(sa.SaError) as e:
+        sa.sa_sparse_prefill(ctx, 256, 256, 256, ix, 256, None)
+    assert "workspace" in str(e.value)
+    with pytest.raises(sa.SaError) as e:
+        sa.sa_sparse_decode(ctx, 256, 256, 256, ix, 32768, 256, None)
+    assert e.value.status == 1
+    sa.sa_destroy(ctx)
+
+
+def test_decode_rejects_positions_outside_the_kv_head_stride():
+    # generated keys live at rows N..pos of every KV head: with the default stride (N rows) there
+    # is no such row, with room for 16 more rows positions N..N+15 pass the check
+    N = 32768
+    ix = sa.SaIndex(*([256] * 7))
+    ctx = sa.sa_create(_cfg())
+    with pytest.raises(sa.SaError) as e:
+        sa.sa_sparse_decode(ctx, 256, 256, 256, ix, N, 256, None)
+    assert e.value.status == 1 and "kv_head_stride" in str(e.value)
+    sa.sa_destroy(ctx)
+    ctx = sa.sa_create(_cfg(kv_head_stride=(N + 16) * 128))
+    with pytest.raises(sa.SaError) as e:
+        sa.sa_sparse_decode(ctx, 256, 256, 256, ix, N + 16, 256, None)
+    assert "kv_head_stride" in str(e.value)
+    with pytest.raises(sa.SaError) as e:      # in range: the next check (workspace) is reached
+        sa.sa_sparse_decode(ctx, 256, 256, 256, ix, N + 15, 256, None)
+    assert "workspace" in str(e.value)
     sa.sa_destroy(ctx)
