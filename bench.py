@@ -114,6 +114,36 @@ def run_workload(name, steps, warmup, layers, with_cpu, sample_rows, with_dense=
     t_est, t_idx, t_attn = ph.mean(0)
     log(f"[{name}] ms/step wall {wall_ms / steps:.3f}; estimate {t_est:.3f} index {t_idx:.3f} attention {t_attn:.3f}")
 
+    # every resident layer once more, each with its own events: the per-layer spread of the sweep
+    # (the K timed steps above cycle the layers from the first one and cover them all only when
+    # K >= layers)
+    sweep = None
+    if layers > 2:
+        evl = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(layers)]
+        for l in range(layers):
+            step(l, evl[l])
+        torch.cuda.synchronize()
+        pl = np.array([[e[k].elapsed_time(e[k + 1]) for k in range(3)] for e in evl])
+        tot = pl.sum(1)
+        sweep = {"layers": layers, "ms_per_layer_mean": float(tot.mean()), "ms_per_layer_p95": float(np.percentile(tot, 95)),
+                 "ms_per_layer_min": float(tot.min()), "ms_per_layer_max": float(tot.max()),
+                 "attention_ms_mean": float(pl[:, 2].mean()), "attention_ms_p95": float(np.percentile(pl[:, 2], 95)),
+                 "estimate_ms_mean": float(pl[:, 0].mean()), "index_ms_mean": float(pl[:, 1].mean()),
+                 "ms_per_layer": [round(float(x), 4) for x in tot]}
+        # the first two layers alone, cycled, with all layers still resident: separates what the
+        # seeds of the other layers cost from what the larger resident set costs
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for i in range(4):
+            step(i % 2)
+        e0.record()
+        for i in range(16):
+            step(i % 2)
+        e1.record()
+        torch.cuda.synchronize()
+        sweep["first_two_layers_cycled_ms_per_layer"] = e0.elapsed_time(e1) / 16
+        log(f"[{name}] {layers}-layer sweep: mean {tot.mean():.3f} p95 {np.percentile(tot, 95):.3f} min {tot.min():.3f} "
+            f"max {tot.max():.3f} ms/layer; layers 0-1 cycled alone {sweep['first_two_layers_cycled_ms_per_layer']:.3f}")
+
     # the same step with estimator and index builder as one call (interleaved on two streams)
     def step1(l, ev=None):
         Q, K, V, _ = resident[l % layers]
@@ -142,17 +172,17 @@ def run_workload(name, steps, warmup, layers, with_cpu, sample_rows, with_dense=
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         graphs = []
-        for l in range(layers):
+        for l in range(min(layers, max(steps, 1))):
             g = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g, stream=side):
                 step(l)
             graphs.append(g)
         for i in range(warmup):
-            graphs[i % layers].replay()
+            graphs[i % len(graphs)].replay()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(steps):
-            graphs[i % layers].replay()
+            graphs[i % len(graphs)].replay()
         torch.cuda.synchronize()
         wallg_ms = (time.perf_counter() - t0) * 1e3
         log(f"[{name}] graph replay of the three calls: ms/step wall {wallg_ms / steps:.3f}")
@@ -172,6 +202,47 @@ def run_workload(name, steps, warmup, layers, with_cpu, sample_rows, with_dense=
         for pp, ch in zip(planted, ses.pattern.cpu().tolist()):
             if pp >= 0:
                 confusion[pp, ch] += 1
+    # The attention kernel's two regimes on layer 0: the tile loop alone (the same index with its
+    # diagonal lists emptied) against its MFMA roof, and what the diagonals add against the memory
+    # roof (each (wave, diagonal) tile fetches 32 K rows and 32 V rows that nothing else uses).
+    Q, K, V, _ = resident[0]
+    ses.estimate(Q, K)
+    ses.build_index(ov)
+    c_full = ses.prefill_counted(Q, K, V, O)
+    saved_n_offs = ses.n_offs.clone()
+
+    def time_prefill(n=6):
+        for _ in range(2):
+            ses.prefill(Q, K, V, O)
+        a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a0.record()
+        for _ in range(n):
+            ses.prefill(Q, K, V, O)
+        a1.record()
+        torch.cuda.synchronize()
+        return a0.elapsed_time(a1) / n
+
+    t_full = time_prefill()
+    ses.n_offs.zero_()
+    c_tile = ses.prefill_counted(Q, K, V, O)
+    t_tile = time_prefill()
+    ses.n_offs.copy_(saved_n_offs)
+    diag_tiles = c_full[0] - c_tile[0]                 # one 32-key tile per (wave, diagonal)
+    diag_bytes = diag_tiles * 32 * 2 * d * 2           # 32 K rows + 32 V rows of d bf16 each
+    f_tile_loop = 4.0 * d * c_tile[0] * 32 * 32
+    t_diag = max(t_full - t_tile, 1e-6)
+    attn_phases = {
+        "layer": 0, "attention_ms": t_full,
+        "tile_loop": {"ms": t_tile, "flop_on_tiles": f_tile_loop, "TFLOPs_on_tiles": f_tile_loop / t_tile / 1e9,
+                      "frac_of_bf16_peak": f_tile_loop / t_tile / 1e9 / PEAK_BF16_TFLOPS,
+                      "how": "same index with n_offs = 0 (no diagonal phase)"},
+        "diagonals": {"ms": t_diag, "bytes": diag_bytes, "GBps": diag_bytes / t_diag / 1e6,
+                      "frac_of_hbm_peak": diag_bytes / t_diag / 1e6 / PEAK_HBM_GBS,
+                      "kept_pairs": c_full[1] - c_tile[1],
+                      "how": "difference to the full call; bytes = 32 K + 32 V rows per (wave, diagonal) tile"},
+    }
+    log(f"[{name}] attention {t_full:.3f} ms = tile loop {t_tile:.3f} ms ({attn_phases['tile_loop']['TFLOPs_on_tiles']:.0f} TFLOP/s on tiles) "
+        f"+ diagonals {t_diag:.3f} ms ({diag_bytes / 1e9:.2f} GB, {attn_phases['diagonals']['GBps']:.0f} GB/s)")
     f_mask = 4.0 * d * float(np.mean(kept))
     f_tiles = 4.0 * d * float(np.mean(tiles)) * 32 * 32   # counter unit: one 32 x 32 sub-tile
     f_dense = 4.0 * d * Hq * N * (N + 1) / 2.0
@@ -191,6 +262,8 @@ def run_workload(name, steps, warmup, layers, with_cpu, sample_rows, with_dense=
         "mfma_frac_of_peak_on_tiles": f_tiles / t_attn / 1e9 / PEAK_BF16_TFLOPS,
         "estimator": {"algorithmic_bytes": est_bytes, "GBps": est_bytes / t_est / 1e6,
                       "frac_of_hbm_peak": est_bytes / t_est / 1e6 / PEAK_HBM_GBS},
+        "attention_phases": attn_phases,
+        "layer_sweep": sweep,
         "pattern_confusion_planted_x_chosen": confusion.tolist(),
         "paper_context": {"ttft_s_whole_model_2xA5000": PAPER_TTFT_S.get(name)},
     }
@@ -482,7 +555,9 @@ def main():
     ap.add_argument("--steps", type=int, default=8)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="cfg5", help="cfg1..cfg5; cfg5 = 128K tokens, cfg3 = 32K")
-    ap.add_argument("--layers", type=int, default=2, help="distinct seeded layers kept resident (cfg5 sweep: 32)")
+    ap.add_argument("--layers", type=int, default=0,
+                    help="distinct seeded layers kept resident and cycled by the steps; 0 = 32 for cfg5 (the "
+                         "benchmark's 32-layer sweep with independent seeds), 2 otherwise")
     ap.add_argument("--also", default="cfg3", help="second workload reported under 'also' ('' to skip)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--prewarm", type=float, default=PREWARM_S,
@@ -541,6 +616,8 @@ def main():
     if a.search:
         run_search(a.search, not a.no_cpu_baseline)
         return
+    if a.layers <= 0:
+        a.layers = 32 if a.workload == "cfg5" else 2
     bsel = 1 if a.block_select == "row" else 0
     fpat = None if a.force_pattern is None else {"T": 0, "IS": 1, "BC": 2}[a.force_pattern]
     dsel = 1 if a.diagonals == "blocks" else 0
@@ -559,6 +636,8 @@ def main():
         traffic = json.load(open(tp)).get("sparse_prefill_kernel_hbm_bytes_per_launch")
     from harness import gen
     wl = gen.WORKLOADS[a.workload]
+    # what the attention kernel cannot avoid moving: Q read and O written once, K and V read once
+    compulsory = 2 * (2 * wl.n_q_heads * wl.seq_len * wl.head_dim) + 2 * (2 * wl.n_kv_heads * wl.seq_len * wl.head_dim)
     out = {
         "metric": "sparse prefill attention ms/layer (estimate + index + attention)",
         "value": round(main_res["ms_per_step"], 4), "unit": "ms/layer",
@@ -575,7 +654,8 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "sparse_prefill_kernel",
                      "achieved": round(main_res["tflops"]["kept"], 2), "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(main_res["tflops"]["kept"] / PEAK_BF16_TFLOPS, 4),
-                     "traffic": traffic,
+                     "traffic": traffic, "compulsory_bytes": compulsory,
+                     "traffic_over_compulsory": None if not traffic else round(traffic / compulsory, 2),
                      "achieved_on_computed_tiles": round(main_res["tflops"]["tiles"], 2),
                      "frac_on_computed_tiles": round(main_res["mfma_frac_of_peak_on_tiles"], 4)},
         "cpu_baseline": main_res.pop("cpu_baseline", None),

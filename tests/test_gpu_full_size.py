@@ -13,17 +13,40 @@ import paper_2412_06198_amd as sa
 pytestmark = pytest.mark.gpu
 
 
-def _whole_path(name, n_rows, margin_check=True, wl=None):
+SENTINEL = 30000.0      # no attention output comes near it: |O| is bounded by max |V| (a few units)
+
+
+def _item_rows(rng, N, extra):
+    """One row in every 128-row work item of the attention kernel (the same rows for every head, so
+    every (head, item) pair is sampled), plus `extra` random rows and the first / middle / last."""
+    starts = np.arange(0, N, 128)
+    per_item = starts + rng.integers(0, np.minimum(128, N - starts))
+    rows = np.concatenate([per_item, rng.choice(N, extra, replace=False), [0, N // 2 + 1, N - 1]])
+    return np.unique(rows).astype(np.int32)
+
+
+def _check_prefill(ses, data, b, got, Q, K, V, rows, what):
+    """sa_sparse_prefill on the index the session holds: every output element is written (O starts
+    as a sentinel no result can equal) and the sampled rows match the oracle on that index."""
+    O = torch.full_like(Q, SENTINEL)
+    ses.prefill(Q, K, V, O)
+    torch.cuda.synchronize()
+    assert bool((O.float().abs() < 1e3).all()), f"{what}: some output rows were never written"
+    ref, ws, _ = orc.masked_rows(data["Q"], data["K"], data["V"], b, got, rows=rows)
+    assert np.abs(ws - 1).max() < 1e-9
+    check_attention(host_f64(O[:, torch.from_numpy(rows.astype(np.int64)).cuda()]), ref, what)
+    return O
+
+
+def _whole_path(name, n_rows, margin_check=True, wl=None, twice=False):
     print(f"case full-size {name}", flush=True)
     wl = gen.WORKLOADS[name] if wl is None else wl
     data = gen.generate(wl)
     N, b, w, Hq = wl.seq_len, wl.block, wl.last_q, wl.n_q_heads
     ses = sa.Session(Hq, wl.n_kv_heads, N, b, w, keep=wl.keep)
     Q, K, V = dev_bf16(data["Q"]), dev_bf16(data["K"]), dev_bf16(data["V"])
-    O = torch.empty_like(Q)
     ses.estimate(Q, K)
     ses.build_index(None)
-    ses.prefill(Q, K, V, O)
     v, s, blk = download_scores(ses)
     got = download_index(ses)
     print("  gpu done; oracle estimate", flush=True)
@@ -54,14 +77,23 @@ def _whole_path(name, n_rows, margin_check=True, wl=None):
                 lo = min(sc[list(a | c)])
                 for j in a ^ c:
                     assert abs(sc[j] - lo) <= 2e-3 * lo, (h, j)
-    # 4. attention on sampled rows, oracle evaluated on the GPU's index
+    # 4. attention, oracle evaluated on the GPU's index: a row of every 128-row item of every head
+    #    plus random rows; every element of O written
     rng = np.random.Generator(np.random.Philox(key=[wl.seed, 5]))
-    rows = np.sort(np.concatenate([rng.choice(N, n_rows - 3, replace=False), [0, N // 2 + 1, N - 1]])).astype(np.int32)
-    rows = np.unique(rows)
-    ref, ws, _ = orc.masked_rows(data["Q"], data["K"], data["V"], b, got, rows=rows)
-    assert np.abs(ws - 1).max() < 1e-9
-    check_attention(host_f64(O[:, torch.from_numpy(rows.astype(np.int64)).cuda()]), ref, name)
-    return ses, (Q, K, V, O), got
+    rows = _item_rows(rng, N, n_rows)
+    print(f"  oracle attention on {rows.size} rows per head", flush=True)
+    O = _check_prefill(ses, data, b, got, Q, K, V, rows, name)
+    if twice:
+        # the same inputs give the same bytes, run to run: scores, index and output
+        ses.estimate(Q, K)
+        ses.build_index(None)
+        O2 = torch.full_like(Q, SENTINEL)
+        ses.prefill(Q, K, V, O2)
+        for a, c in zip(download_scores(ses), (v, s, blk)):
+            assert a.tobytes() == c.tobytes()
+        assert_index_equal(download_index(ses), got)
+        assert torch.equal(O, O2)
+    return ses, (Q, K, V, O), got, data
 
 
 def test_cfg2_16k():
@@ -77,7 +109,29 @@ def test_cfg4_64k():
 
 
 def test_cfg5_128k_one_layer():
-    _whole_path("cfg5", 48)
+    _whole_path("cfg5", 48, twice=True)
+
+
+@pytest.mark.parametrize("forced", [orc.INTERVAL_SLASH, orc.TRIANGULAR])
+def test_cfg5_128k_every_head_one_pattern(forced):
+    # 8 KV heads at 128K: two work queues share a KV head (the queue mapping that only this size
+    # reaches), and with every head Interval-Slash every item runs the diagonal phase.  Index
+    # byte-identical to the oracle under the override, attention on a row of every item of every head.
+    print(f"case cfg5 forced pattern {forced}", flush=True)
+    wl = gen.WORKLOADS["cfg5"]
+    data = gen.generate(wl)
+    N, b, w, Hq = wl.seq_len, wl.block, wl.last_q, wl.n_q_heads
+    ses = sa.Session(Hq, wl.n_kv_heads, N, b, w, keep=wl.keep)
+    Q, K, V = dev_bf16(data["Q"]), dev_bf16(data["K"]), dev_bf16(data["V"])
+    ses.estimate(Q, K)
+    ses.build_index([forced] * Hq)
+    v, s, blk = download_scores(ses)
+    got = download_index(ses)
+    want = orc.build_index(v, s, blk, N, b, w, orc.default_budgets(N, b, wl.keep), override=[forced] * Hq)
+    assert_index_equal(got, want)
+    assert (got.pattern == forced).all()
+    rng = np.random.Generator(np.random.Philox(key=[wl.seed, 6 + forced]))
+    _check_prefill(ses, data, b, got, Q, K, V, _item_rows(rng, N, 16), f"cfg5 forced {forced}")
 
 
 def test_ragged_33k_whole_path():

@@ -407,3 +407,41 @@ def test_planted_recovery_small_mixed():
     for h, p in enumerate(data["plants"]):
         if p.pattern in (T, IS):
             assert auto[h] == p.pattern
+
+
+@pytest.mark.parametrize("N,b,bud", [
+    (1024, 64, orc.Budgets(1, 3, 40, 4, 30)),
+    (1024, 64, orc.Budgets(2, 16, 40, 4, 16)),                      # band = everything: the Triangular count rules
+    (2048, 128, orc.Budgets(1, 2, 64, 6, 60, block_select=1)),      # per-row shares round up
+    (1024, 64, orc.Budgets(1, 2, 40, 5, 20, diagonal_select=1)),    # widened diagonals: two key blocks per offset
+    (1024, 64, orc.Budgets(0, 1, 40, 1024, 16, diagonal_select=1)), # every offset selected
+])
+def test_block_capacity_bounds_every_index_the_oracle_builds(N, b, bud):
+    # block_capacity is a buffer size; it is pinned against the blocks counted in indices the oracle
+    # itself builds under every override, and against the Triangular set written out with numpy
+    nb, w, H = N // b, 32, 3
+    cap = orc.block_capacity(N, b, bud)
+    R, Cc = np.arange(nb)[:, None], np.arange(nb)[None, :]
+    tri = int(((Cc <= R) & ((Cc < bud.sink_blocks) | (R - Cc < bud.local_blocks))).sum())
+    assert cap >= tri
+    rng = np.random.default_rng(5)
+    seen = 0
+    for trial in range(4):
+        v = rng.random((H, N), dtype=np.float32)
+        s = rng.random((H, N), dtype=np.float32)
+        blk = np.tril(rng.random((H, nb, nb), dtype=np.float32))
+        if trial == 1:    # offsets spread so that widened diagonals touch as many distinct blocks as they can
+            s[:] = 0
+            s[:, (np.arange(N) % b) == b // 2] = 1
+        for pat in (0, 1, 2):
+            ix = orc.build_index(v, s, blk, N, b, w, bud, override=[pat] * H)
+            cnt = ix.rowptr[:, nb]
+            assert (cnt <= cap).all(), (pat, cnt, cap)
+            assert ((ix.blkcols >= 0).sum(1) == cnt).all()
+            if pat == 0:
+                assert (cnt == tri).all()
+            seen = max(seen, int(cnt.max()))
+    if not bud.diagonal_select and bud.block_select != 1:
+        assert seen == cap            # tight: some pattern fills the buffer
+    elif bud.block_select == 1:       # per-row shares: each of the nb rows rounds up by less than one block
+        assert bud.k_blocks <= seen <= cap and cap - bud.k_blocks <= nb
