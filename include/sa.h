@@ -199,6 +199,19 @@ sa_status sa_sparse_prefill_counted(sa_ctx *ctx, const void *Q, const void *K, c
 sa_status sa_sparse_decode(sa_ctx *ctx, const void *q, const void *K, const void *V, sa_index idx,
                            int64_t pos, void *o, void *hip_stream);
 
+/* sa_sparse_decode for callers that cannot allocate device memory or attach a workspace (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments, same
+ * kernels, same output bytes, but the partial results of the step live in a static device array
+ * inside the library (270336 bytes per GPU, held until the process ends) instead of ctx's
+ * workspace, which need not be attached.  The call allocates and frees nothing.  Limit: n_q_heads
+ * times the split count the library picks must not exceed 512 partial results (every context
+ * sa_create accepts today fits; a larger one gets SA_ERR_UNSUPPORTED).  All calls on one GPU - from
+ * any context or thread - share that array: calls that overlap in time on one GPU race, so keep
+ * them on one stream or order them with events.  Nothing in the array needs clearing between calls
+ * (every slot a call reads it has written first). */
+sa_status sa_sparse_decode_static(sa_ctx *ctx, const void *q, const void *K, const void *V, sa_index idx,
+                                  int64_t pos, void *o, void *hip_stream);
+
 /* Offline pattern search, "Kernel-Aware Sparse Pattern Search Algorithm" (Alg. 1), one head at a
  * time.  Candidates: the three patterns, each with one integer size (its search space):
  *   SA_TRIANGULAR      local_blocks = x,                       1 <= x <= nb

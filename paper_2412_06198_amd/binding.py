@@ -75,6 +75,7 @@ def library():
         lib.sa_sparse_prefill.argtypes = [vp, vp, vp, vp, SaIndex, vp, vp]
         lib.sa_sparse_prefill_counted.argtypes = [vp, vp, vp, vp, SaIndex, vp, vp, vp]
         lib.sa_sparse_decode.argtypes = [vp, vp, vp, vp, SaIndex, C.c_int64, vp, vp]
+        lib.sa_sparse_decode_static.argtypes = [vp, vp, vp, vp, SaIndex, C.c_int64, vp, vp]
         lib.sa_search_scratch_bytes.argtypes = [vp, C.POINTER(C.c_size_t)]
         lib.sa_search_patterns.argtypes = [vp, vp, vp, vp, SaScores, C.c_int64, C.c_int64, vp, C.c_size_t,
                                            C.POINTER(SaSearchHead), vp]
@@ -82,7 +83,7 @@ def library():
                   "sa_workspace_bytes", "sa_set_workspace", "sa_estimate_patterns",
                   "sa_build_index", "sa_sparse_prefill", "sa_sparse_prefill_counted",
                   "sa_search_scratch_bytes", "sa_search_patterns", "sa_sparse_decode",
-                  "sa_estimate_and_index"):
+                  "sa_sparse_decode_static", "sa_estimate_and_index"):
             getattr(lib, f).restype = st
         _lib = lib
     return _lib
@@ -183,6 +184,11 @@ def sa_sparse_decode(ctx, q, K, V, index: SaIndex, pos, o, stream=None):
     _check(library().sa_sparse_decode(ctx, _ptr(q), _ptr(K), _ptr(V), index, C.c_int64(int(pos)), _ptr(o), stream), ctx)
 
 
+def sa_sparse_decode_static(ctx, q, K, V, index: SaIndex, pos, o, stream=None):
+    _check(library().sa_sparse_decode_static(ctx, _ptr(q), _ptr(K), _ptr(V), index, C.c_int64(int(pos)), _ptr(o),
+                                             stream), ctx)
+
+
 class SaSearchHead(C.Structure):
     _fields_ = [("pattern", C.c_int32), ("param", C.c_int32 * 3), ("pairs", C.c_int64 * 3),
                 ("err", C.c_double * 3)]
@@ -281,6 +287,11 @@ class Session:
     def decode(self, q, K, V, pos, o):
         """One decode step at position pos >= seq_len over the current index."""
         sa_sparse_decode(self.ctx, q, K, V, self.index(), pos, o, self.stream())
+
+    def decode_static(self, q, K, V, pos, o):
+        """The same step through the entry point that keeps its partial results in the library's
+        static device array (no workspace needed, nothing allocated)."""
+        sa_sparse_decode_static(self.ctx, q, K, V, self.index(), pos, o, self.stream())
 
     def search_patterns(self, Q, K, V, target_pairs, eps_pairs):
         """Alg. 1 on the scores of the last estimate(): one dict per head."""

@@ -346,9 +346,8 @@ sa_status sa_sparse_prefill_counted(sa_ctx *c, const void *Q, const void *K, con
   return prefill_common(c, Q, K, V, idx, O, counters_dev, stream);
 }
 
-sa_status sa_sparse_decode(sa_ctx *c, const void *q, const void *K, const void *V, sa_index idx,
-                           int64_t pos, void *o, void *stream) {
-  if (!c) return SA_ERR_INVALID_ARG;
+static sa_status check_decode_args(sa_ctx *c, const void *q, const void *K, const void *V, sa_index idx,
+                                   int64_t pos, void *o) {
   if (!q || !K || !V || !o || !idx.n_cols || !idx.cols || !idx.n_offs || !idx.offs || !idx.rowptr ||
       !idx.blkcols)
     return fail(c, SA_ERR_INVALID_ARG, "null pointer");
@@ -360,8 +359,31 @@ sa_status sa_sparse_decode(sa_ctx *c, const void *q, const void *K, const void *
   // rows (and leave the buffer behind the last head)
   if ((pos + 1) * c->sh.kv_rs > c->sh.kv_hs)
     return fail(c, SA_ERR_INVALID_ARG, "kv_head_stride leaves no room for key rows up to pos");
+  return SA_OK;
+}
+
+sa_status sa_sparse_decode(sa_ctx *c, const void *q, const void *K, const void *V, sa_index idx,
+                           int64_t pos, void *o, void *stream) {
+  if (!c) return SA_ERR_INVALID_ARG;
+  const sa_status s = check_decode_args(c, q, K, V, idx, pos, o);
+  if (s != SA_OK) return s;
   if (!c->have_ws) return fail(c, SA_ERR_INVALID_ARG, "no workspace attached");
-  return hip_result(c, sa::launch_sparse_decode(c->sh, c->ws, (const uint16_t *)q, (const uint16_t *)K,
+  return hip_result(c, sa::launch_sparse_decode(c->sh, c->ws.dec_part, (const uint16_t *)q, (const uint16_t *)K,
+                                                (const uint16_t *)V, idx, (int)pos, (uint16_t *)o,
+                                                (hipStream_t)stream));
+}
+
+sa_status sa_sparse_decode_static(sa_ctx *c, const void *q, const void *K, const void *V, sa_index idx,
+                                  int64_t pos, void *o, void *stream) {
+  if (!c) return SA_ERR_INVALID_ARG;
+  const sa_status s = check_decode_args(c, q, K, V, idx, pos, o);
+  if (s != SA_OK) return s;
+  if (sa::decode_partial_bytes(c->sh) > sa::decode_static_bytes())
+    return fail(c, SA_ERR_UNSUPPORTED, "n_q_heads x decode splits exceeds the static scratch (512 partials)");
+  float *partials = nullptr;
+  const hipError_t e = sa::decode_static_scratch(&partials);
+  if (e != hipSuccess) return hip_result(c, e);
+  return hip_result(c, sa::launch_sparse_decode(c->sh, partials, (const uint16_t *)q, (const uint16_t *)K,
                                                 (const uint16_t *)V, idx, (int)pos, (uint16_t *)o,
                                                 (hipStream_t)stream));
 }

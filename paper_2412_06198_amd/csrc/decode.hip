@@ -6,12 +6,22 @@
 // head, nothing reused, so the kernel is laid out for HBM: every key is read by 16 lanes as one
 // 256-byte row of K and one of V, sixteen keys per workgroup step, the key list of a head split
 // over several workgroups whose partial (max, sum, output) triples a second kernel merges.
+#include <mutex>
+
 #include "sa_internal.h"
 
 namespace sa {
 namespace {
 
 constexpr int kPartStride = 132;  // floats per partial: max, sum, 2 unused, 128 outputs
+
+// Partials of the variant that allocates nothing (sa_sparse_decode_static): room for the largest
+// head count x split count the launcher ever picks (Hq * splits <= 512), 270336 bytes on every GPU
+// the library runs on, held until the process ends.  In host code this name is only a stand-in for
+// the symbol: the device address comes from hipGetSymbolAddress, once per device.
+constexpr int kStaticPartials = 512;
+static __device__ __align__(256) float scratch[kStaticPartials * kPartStride];
+constexpr int kMaxDevices = 64;
 
 struct DecArgs {
   const uint16_t *q, *K, *V;
@@ -173,13 +183,36 @@ int decode_splits(const Shape &sh) {
 
 size_t decode_partial_bytes(const Shape &sh) { return (size_t)sh.Hq * decode_splits(sh) * kPartStride * 4; }
 
-hipError_t launch_sparse_decode(const Shape &sh, const Workspace &ws, const uint16_t *q, const uint16_t *K,
+size_t decode_static_bytes() { return sizeof(float) * kStaticPartials * kPartStride; }
+
+// Device address of `scratch` on the current device: asked for once per device (each GPU holds its
+// own copy of the array at its own address) and kept.
+hipError_t decode_static_scratch(float **out) {
+  static std::mutex mu;
+  static float *ptr[kMaxDevices] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr[dev]) {
+    float *d = nullptr;
+    e = hipGetSymbolAddress((void **)&d, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!d) return hipErrorInvalidSymbol;
+    ptr[dev] = d;
+  }
+  *out = ptr[dev];
+  return hipSuccess;
+}
+
+hipError_t launch_sparse_decode(const Shape &sh, float *partials, const uint16_t *q, const uint16_t *K,
                                 const uint16_t *V, sa_index idx, int pos, uint16_t *o, hipStream_t st) {
   DecArgs a;
   a.q = q; a.K = K; a.V = V; a.o = o;
   a.n_cols = idx.n_cols; a.cols = idx.cols; a.n_offs = idx.n_offs; a.offs = idx.offs;
   a.rowptr = idx.rowptr; a.blkcols = idx.blkcols;
-  a.part = ws.dec_part;
+  a.part = partials;
   a.Hq = sh.Hq; a.g = sh.g; a.N = sh.N; a.b = sh.b; a.nb = sh.nb; a.k_v = sh.k_v; a.k_s = sh.k_s;
   a.cap_b = sh.cap_b; a.S = decode_splits(sh); a.pos = pos;
   a.kv_hs = sh.kv_hs; a.kv_rs = sh.kv_rs;

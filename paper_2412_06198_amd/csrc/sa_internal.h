@@ -87,8 +87,11 @@ hipError_t launch_build_index(const Shape &sh, const Workspace &ws, sa_scores in
 hipError_t launch_index_stage(const Shape &sh, const Workspace &ws, sa_scores in, const Override &ov,
                               sa_index out, IndexStage stage, hipStream_t st, bool lazy = false);
 size_t decode_partial_bytes(const Shape &sh);
-hipError_t launch_sparse_decode(const Shape &sh, const Workspace &ws, const uint16_t *q, const uint16_t *K,
+// partials: decode_partial_bytes(sh) bytes of device memory (the context's workspace, or the static array)
+hipError_t launch_sparse_decode(const Shape &sh, float *partials, const uint16_t *q, const uint16_t *K,
                                 const uint16_t *V, sa_index idx, int pos, uint16_t *o, hipStream_t st);
+size_t decode_static_bytes();                       // size of the library's static decode scratch
+hipError_t decode_static_scratch(float **out);      // its address on the current device
 hipError_t launch_sparse_prefill(const Shape &sh, const Workspace &ws, const uint16_t *Q,
                                  const uint16_t *K, const uint16_t *V, sa_index idx, uint16_t *O,
                                  unsigned long long *counters, hipStream_t st);
