@@ -639,14 +639,28 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
     SA_DIAG_COPY(Kh, o, krow, kchunk, ((4 * n_) & 15) << 4, ldsKw)                               \
   }
 #define SA_DIAG_ISSUE_V(o) SA_DIAG_COPY(Vh, o, (unsigned)(vrow * (int)p.kv_rs * 2), vchunk, 0, ldsVw)
-    if (nd > 0) {
-      const int o0 = (int)uload(offp, 0);
+    // An offset whose (at most two) key tiles are both kept by the CSR contributes nothing here -
+    // every one of its entries was counted by those tiles - so it is skipped before any copy is
+    // issued.  The test is wave-uniform; `e` walks the offsets that are left.
+    auto dead = [&](int o_) {
+      const int jb_ = r0 - o_;
+      const int kta_ = max(jb_, 0) >> 6, ktb_ = max(jb_ + 31, 0) >> 6;
+      return (((kw[kta_ >> 5] >> (kta_ & 31)) & (kw[ktb_ >> 5] >> (ktb_ & 31))) & 1u) != 0u;
+    };
+    auto next_live = [&](int e_) {
+      while (e_ < nd && __builtin_amdgcn_readfirstlane((int)dead((int)uload(offp, e_)))) ++e_;
+      return e_;
+    };
+    int e = next_live(0);
+    if (e < nd) {
+      const int o0 = (int)uload(offp, e);
       SA_DIAG_ISSUE_K(o0);
       SA_DIAG_ISSUE_V(o0);
     }
-    for (int e = 0; e < nd; ++e) {
+    while (e < nd) {
       const int o = (int)uload(offp, e);
-      const int onext = (int)uload(offp, min(e + 1, nd - 1));
+      const int e_nxt = next_live(e + 1);
+      const int onext = (int)uload(offp, min(e_nxt, nd - 1));
       const int jb = r0 - o;
       f32x16 sd;
 #pragma unroll
@@ -661,7 +675,7 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
       for (int r = 1; r < 16; ++r) sv = (r == rstar) ? sd[r] : sv;
       const bool cbit = (cw >> q) & 1u;
       // the K tile has been read into the matrix pipe: the next offset's K may land
-      if (e + 1 < nd) SA_DIAG_ISSUE_K(onext);
+      if (e_nxt < nd) SA_DIAG_ISSUE_K(onext);
       // validity of (query iq, key iq - o)
       const int j = iq - o;
       bool valid = holder && j >= 0 && iq < N;
@@ -693,7 +707,7 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
       const __bf16 pvb = (__bf16)pv, zb = (__bf16)0.f;
       // V of this offset has landed once only the 8 copies of the next K, issued after it, are
       // outstanding
-      if (e + 1 < nd) __builtin_amdgcn_s_waitcnt(0x0F78);  // vmcnt(8)
+      if (e_nxt < nd) __builtin_amdgcn_s_waitcnt(0x0F78);  // vmcnt(8)
       else __builtin_amdgcn_s_waitcnt(0x0F70);                       // vmcnt(0)
       // P^T is diagonal: slot e2 of k-step u is register 8u+e2
 #pragma unroll
@@ -711,7 +725,8 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
         }
       }
       // the V tile has been read: the next offset's V may land
-      if (e + 1 < nd) SA_DIAG_ISSUE_V(onext);
+      if (e_nxt < nd) SA_DIAG_ISSUE_V(onext);
+      e = e_nxt;
     }
 #undef SA_DIAG_ISSUE_K
 #undef SA_DIAG_ISSUE_V

@@ -51,7 +51,7 @@ __device__ inline void store_split(float *means_head, int R, int d, float x) {
 // a thread are in flight before the first sum.  The kernel is pure HBM streaming and runs beside
 // the window passes (vector ALU bound): it is launched with kQMeanLdsPad* bytes of unused dynamic
 // LDS so that it never holds more than a few wave slots of a compute unit.
-constexpr int kQMeanLdsPad128 = 40 * 1024, kQMeanLdsPad64 = 32 * 1024;  // by block size: measured best
+constexpr int kQMeanLdsPad128 = 32 * 1024, kQMeanLdsPad64 = 32 * 1024;  // measured best (16-96 KB swept)
 
 template <int RPT>
 __global__ __launch_bounds__(256) void q_block_mean_kernel(const uint16_t *__restrict__ Q, Shape sh,
@@ -122,6 +122,20 @@ __device__ inline void load_qwin(const uint16_t *__restrict__ Q, const Shape &sh
                "s"(ldsb)                                                                              \
                : "memory")
 
+// The window passes keep kStages K tiles in LDS: tile t is multiplied while the copies of the
+// next kStages - 2 tiles are in flight (one tile of lead per workgroup left the passes waiting for
+// memory latency most of the time: a workgroup only had 16 KB on its way).
+constexpr int kStages = 3;
+
+// Wait until this wave's copies of tile t have landed while up to `ahead` younger tiles (four copy
+// instructions each) may still be in flight.  Vector memory operations of a kind retire in issue
+// order, so at most 4 * ahead outstanding operations means the older copies are complete.
+__device__ inline void wait_tile(int ahead) {
+  if (ahead >= 2) __builtin_amdgcn_s_waitcnt(0x0F78);       // vmcnt(8)
+  else if (ahead == 1) __builtin_amdgcn_s_waitcnt(0x0F74);  // vmcnt(4)
+  else __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0)
+}
+
 struct KTileCopy {
   unsigned voff;   // per-lane byte offset inside a 16-row slab of K
   unsigned lds0;   // LDS byte address of this wave's first row in buffer 0
@@ -147,12 +161,12 @@ __device__ inline bf16x8 k_frag(const uint16_t *tile, unsigned kbase, int gg, in
 }
 
 // pass 1: grid (nchunks, Hkv, ceil(g/4)), 256 threads.
-__global__ __launch_bounds__(256) void window_stats_kernel(const uint16_t *__restrict__ Q,
+__global__ __launch_bounds__(256, 2) void window_stats_kernel(const uint16_t *__restrict__ Q,
                                                            const uint16_t *__restrict__ K, Shape sh,
                                                            float c, float2 *__restrict__ part,
                                                            float *__restrict__ s_out,
                                                            float *__restrict__ kblk) {
-  __shared__ __attribute__((aligned(16))) uint16_t Ks[2][64 * 128];
+  __shared__ __attribute__((aligned(16))) uint16_t Ks[kStages][64 * 128];
   __shared__ float ksum[2][4][kHeadDim];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -177,6 +191,9 @@ __global__ __launch_bounds__(256) void window_stats_kernel(const uint16_t *__res
 
   bf16x8 qf[2][8];
   load_qwin(Q, sh, hq, lane, qf);
+#pragma unroll
+  for (int s2 = 1; s2 < kStages - 1; ++s2)
+    if (s2 < nt) cp.issue(Kh + (size_t)s2 * 64 * sh.kv_rs, s2);
   float m[2] = {-INFINITY, -INFINITY}, z[2] = {0.f, 0.f};
   const unsigned kbase = (unsigned)(q * 256) | (unsigned)((q & 15) << 4);
 
@@ -187,10 +204,11 @@ __global__ __launch_bounds__(256) void window_stats_kernel(const uint16_t *__res
   int pending = -1;           // block whose four partial sums wait in ksum[pending & 1]
 
   for (int t = 0; t < nt; ++t) {
-    const int cur = t & 1;
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of tile t has landed
-    __syncthreads();
-    if (t + 1 < nt) cp.issue(Kh + (size_t)(t + 1) * 64 * sh.kv_rs, cur ^ 1);
+    const int cur = t % kStages;
+    wait_tile(min(nt - 1 - t, kStages - 2));  // this wave's share of tile t has landed
+    __syncthreads();                          // ... and everybody's; tile t-1 has been read by all
+    if (t + kStages - 1 < nt)
+      cp.issue(Kh + (size_t)(t + kStages - 1) * 64 * sh.kv_rs, (t + kStages - 1) % kStages);
     const uint16_t *Kt = Ks[cur];
     const int j0 = jc0 + 64 * t;
 
@@ -217,54 +235,49 @@ __global__ __launch_bounds__(256) void window_stats_kernel(const uint16_t *__res
       }
     }
 
-    f32x16 acc[2][2];  // [key half][query half]
+    // One 32-key half of the tile at a time: its scores are reduced to (max, sum) before the next
+    // half is multiplied, so only 32 accumulator registers are live (two waves per SIMD fit).
+    // lane = query 32qh+q ; acc[qh][r] <-> key j0 + 32kh + 8(r/4) + 4gg + r%4
+    const bool tail = j0 + 63 > sh.N - sh.w;  // causal masking only in the last tile of the sequence
 #pragma unroll
     for (int kh = 0; kh < 2; ++kh) {
+      f32x16 acc[2];  // [query half]
 #pragma unroll
       for (int qh = 0; qh < 2; ++qh)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[kh][qh][r] = 0.f;
+        for (int r = 0; r < 16; ++r) acc[qh][r] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
         const bf16x8 a = k_frag(Kt, kbase, gg, kh, ks);
 #pragma unroll
         for (int qh = 0; qh < 2; ++qh)
-          acc[kh][qh] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qh][ks], acc[kh][qh], 0, 0, 0);
+          acc[qh] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qh][ks], acc[qh], 0, 0, 0);
       }
-    }
-    // lane = query 32qh+q ; acc[kh][qh][r] <-> key j0 + 32kh + 8(r/4) + 4gg + r%4
-    const bool tail = j0 + 63 > sh.N - sh.w;  // causal masking only in the last tile of the sequence
 #pragma unroll
-    for (int qh = 0; qh < 2; ++qh) {
-      float tmax = -INFINITY;
-      if (tail) {
-        const int jmax = sh.N - sh.w + 32 * qh + q;  // last visible key of this window row
-#pragma unroll
-        for (int kh = 0; kh < 2; ++kh)
+      for (int qh = 0; qh < 2; ++qh) {
+        float tmax = -INFINITY;
+        if (tail) {
+          const int jmax = sh.N - sh.w + 32 * qh + q;  // last visible key of this window row
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const int j = j0 + 32 * kh + 8 * (r / 4) + 4 * gg + (r % 4);
-            if (j > jmax) acc[kh][qh][r] = -INFINITY;
+            if (j > jmax) acc[qh][r] = -INFINITY;
           }
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, acc[qh][r]);
+        // the reference moves only when a row's maximum grew by more than 2^8 (terms stay <= 256)
+        const float m_new = fmaxf(m[qh], tmax * c);
+        if (__any(m_new - m[qh] > 8.f)) {
+          z[qh] *= __builtin_amdgcn_exp2f(m[qh] - ((m_new == -INFINITY) ? 0.f : m_new));
+          m[qh] = m_new;
+        }
+        const float m_ref = (m[qh] == -INFINITY) ? 0.f : m[qh];
+        float sum = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[qh][r], c, -m_ref));
+        z[qh] += sum;
       }
-#pragma unroll
-      for (int kh = 0; kh < 2; ++kh)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, acc[kh][qh][r]);
-      // the reference moves only when a row's maximum grew by more than 2^8 (terms stay <= 256)
-      const float m_new = fmaxf(m[qh], tmax * c);
-      if (__any(m_new - m[qh] > 8.f)) {
-        z[qh] *= __builtin_amdgcn_exp2f(m[qh] - ((m_new == -INFINITY) ? 0.f : m_new));
-        m[qh] = m_new;
-      }
-      const float m_ref = (m[qh] == -INFINITY) ? 0.f : m[qh];
-      float sum = 0.f;
-#pragma unroll
-      for (int kh = 0; kh < 2; ++kh)
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-          sum += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[kh][qh][r], c, -m_ref));
-      z[qh] += sum;
     }
   }
   if (do_means) {
@@ -384,7 +397,7 @@ __global__ __launch_bounds__(256) void window_scores_kernel(const uint16_t *__re
                                                             float c, const float *__restrict__ bias_g,
                                                             float *__restrict__ v_out,
                                                             float *__restrict__ s_out) {
-  __shared__ __attribute__((aligned(16))) uint16_t Ks[2][64 * 128];
+  __shared__ __attribute__((aligned(16))) uint16_t Ks[kStages][64 * 128];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int q = lane & 31, gg = lane >> 5;
@@ -407,6 +420,9 @@ __global__ __launch_bounds__(256) void window_scores_kernel(const uint16_t *__re
 #pragma unroll
   for (int i = 0; i < kWin; ++i)
     bias[i] = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(bias_g[(size_t)hq * kWin + i])));
+#pragma unroll
+  for (int s2 = 1; s2 < kStages - 1; ++s2)
+    if (s2 < nt) cp.issue(Kh + (size_t)s2 * 64 * sh.kv_rs, s2);
   const unsigned kbase = (unsigned)(q * 256) | (unsigned)((q & 15) << 4);
   float *srow = s_out + (size_t)hq * sh.N;
   float run = 0.f, done = 0.f;
@@ -414,10 +430,12 @@ __global__ __launch_bounds__(256) void window_scores_kernel(const uint16_t *__re
   asm volatile("" : "+v"(cv));
 
   for (int t = 0; t < nt; ++t) {
-    const int cur = t & 1;
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    const int cur = t % kStages;
+    // the stores of the previous tiles count like the copies: they only make the wait longer
+    wait_tile(min(nt - 1 - t, kStages - 2));
     __syncthreads();
-    if (t + 1 < nt) cp.issue(Kh + (size_t)(t + 1) * 64 * sh.kv_rs, cur ^ 1);
+    if (t + kStages - 1 < nt)
+      cp.issue(Kh + (size_t)(t + kStages - 1) * 64 * sh.kv_rs, (t + kStages - 1) % kStages);
     const uint16_t *Kt = Ks[cur];
     const int j0 = jc0 + 64 * t;
 
