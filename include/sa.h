@@ -17,9 +17,11 @@
  *     elements; O is written with round-to-nearest-even.
  *   - The caller owns every device buffer (Q, K, V, O, scores, index,
  *     workspace).  Sizes come from the *_bytes queries.  The library never
- *     allocates or frees device memory and never synchronises the host: the
- *     compute calls enqueue kernels on the given HIP stream and return (the
- *     offline search is the exception: the host steers it, see there).
+ *     allocates or frees device memory and the compute calls never synchronise
+ *     the host: they enqueue kernels on the given HIP stream and return.  The
+ *     offline search is the exception on the host side: the host steers it, so
+ *     it waits for the stream after every probe and creates and frees small
+ *     host-memory contexts on the way (still no device memory), see there.
  *     sa_estimate_patterns (and sa_estimate_and_index) runs part of its kernels on a side stream that the
  *     context owns (created by sa_create, default priority); that stream waits
  *     for the given stream at entry and the given stream waits for it at exit,

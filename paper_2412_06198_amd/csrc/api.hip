@@ -77,7 +77,13 @@ sa_status sa_default_budgets(sa_config *cfg, double keep) {
   return SA_OK;
 }
 
-sa_status sa_create(const sa_config *cfg, sa_ctx **out) {
+sa_status sa_create(const sa_config *cfg, sa_ctx **out) { return sa::create_context(cfg, out, true); }
+
+}  // extern "C"
+
+// side_stream == false: a context for callers inside the library that never run the estimator (the
+// probes of the offline search): no stream and no events are created.
+sa_status sa::create_context(const sa_config *cfg, sa_ctx **out, bool side_stream) {
   if (!cfg || !out) return SA_ERR_INVALID_ARG;
   *out = nullptr;
   if (cfg->head_dim != sa::kHeadDim) return SA_ERR_UNSUPPORTED;
@@ -153,7 +159,9 @@ sa_status sa_create(const sa_config *cfg, sa_ctx **out) {
   // Side stream of the estimator (default priority).  Without a usable device the creation
   // fails and the context simply enqueues everything on the caller's stream.
   c->fork = sa::Fork{nullptr, nullptr, nullptr, nullptr};
-  if (hipStreamCreateWithFlags(&c->fork.aux, hipStreamNonBlocking) == hipSuccess) {
+  if (!side_stream) {
+    // everything is enqueued on the caller's stream
+  } else if (hipStreamCreateWithFlags(&c->fork.aux, hipStreamNonBlocking) == hipSuccess) {
     if (hipEventCreateWithFlags(&c->fork.fork, hipEventDisableTiming) != hipSuccess ||
         hipEventCreateWithFlags(&c->fork.mid, hipEventDisableTiming) != hipSuccess ||
         hipEventCreateWithFlags(&c->fork.join, hipEventDisableTiming) != hipSuccess) {
@@ -173,6 +181,8 @@ sa_status sa_create(const sa_config *cfg, sa_ctx **out) {
   *out = c;
   return SA_OK;
 }
+
+extern "C" {
 
 void sa_destroy(sa_ctx *ctx) {
   if (!ctx) return;

@@ -71,6 +71,9 @@ struct sa_ctx {
 
 namespace sa {
 
+// sa_create, optionally without the estimator's side stream and its events
+sa_status create_context(const sa_config *cfg, sa_ctx **out, bool side_stream);
+
 hipError_t launch_estimate(const Shape &sh, const Workspace &ws, const uint16_t *Q,
                            const uint16_t *K, sa_scores out, hipStream_t st, const Fork &fk,
                            bool join_back = true);

@@ -86,7 +86,7 @@ sa_status plan(const sa_ctx *ctx, Sizes *z) {
   sa_config c;
   candidate_config(p, SA_INTERVAL_SLASH, z->x_hi[1], &c);
   sa_ctx *child = nullptr;
-  sa_status st = sa_create(&c, &child);
+  sa_status st = sa::create_context(&c, &child, false);
   if (st != SA_OK) return st;
   st = sa_workspace_bytes(child, &z->ws_child);
   sa_destroy(child);
@@ -166,7 +166,7 @@ sa_status sa_search_patterns(sa_ctx *ctx, const void *Q, const void *K, const vo
       sa_config c;
       candidate_config(ctx->cfg, pattern, x, &c);
       sa_ctx *child = nullptr;
-      sa_status s_ = sa_create(&c, &child);
+      sa_status s_ = sa::create_context(&c, &child, false);  // host memory only: no stream, no events
       if (s_ != SA_OK) return failp(ctx, s_, "search: candidate rejected by sa_create");
       const int32_t ov = pattern;
       s_ = sa_set_workspace(child, ws, z.ws_child);
