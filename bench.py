@@ -54,7 +54,7 @@ def cpu_baseline(orc, data, wl, bud, sample_rows):
 
 
 def run_workload(name, steps, warmup, layers, with_cpu, sample_rows, with_dense=False, block_select=0,
-                 diagonal_select=0, prewarm_s=PREWARM_S, lazy_block_map=0, force_pattern=None):
+                 diagonal_select=0, prewarm_s=PREWARM_S, lazy_block_map=0, force_pattern=None, plain=False):
     import numpy as np
     import torch
 
@@ -118,7 +118,7 @@ def run_workload(name, steps, warmup, layers, with_cpu, sample_rows, with_dense=
     # (the K timed steps above cycle the layers from the first one and cover them all only when
     # K >= layers)
     sweep = None
-    if layers > 2:
+    if layers > 2 and not plain:
         evl = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(layers)]
         for l in range(layers):
             step(l, evl[l])
@@ -153,22 +153,26 @@ def run_workload(name, steps, warmup, layers, with_cpu, sample_rows, with_dense=
         ses.prefill(Q, K, V, O)
         if ev: ev[2].record()
 
-    for i in range(warmup):
-        step1(i)
-    torch.cuda.synchronize()
-    evs1 = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
-    t0 = time.perf_counter()
-    for i in range(steps):
-        step1(i, evs1[i])
-    torch.cuda.synchronize()
-    wall1_ms = (time.perf_counter() - t0) * 1e3
-    ph1 = np.array([[e[k].elapsed_time(e[k + 1]) for k in range(2)] for e in evs1]).mean(0)
-    log(f"[{name}] one-call form{' (block map for the Block-Cluster heads only)' if lazy_block_map else ''}: ms/step wall {wall1_ms / steps:.3f}; estimate+index {ph1[0]:.3f} attention {ph1[1]:.3f}")
+    wall1_ms, ph1 = float('nan') * steps, np.array([float('nan'), float('nan')])
+    if not plain:    # --plain runs only the three-call loop (kernel traces whose averages must match the timed loop)
+        for i in range(warmup):
+            step1(i)
+        torch.cuda.synchronize()
+        evs1 = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+        t0 = time.perf_counter()
+        for i in range(steps):
+            step1(i, evs1[i])
+        torch.cuda.synchronize()
+        wall1_ms = (time.perf_counter() - t0) * 1e3
+        ph1 = np.array([[e[k].elapsed_time(e[k + 1]) for k in range(2)] for e in evs1]).mean(0)
+        log(f"[{name}] one-call form{' (block map for the Block-Cluster heads only)' if lazy_block_map else ''}: ms/step wall {wall1_ms / steps:.3f}; estimate+index {ph1[0]:.3f} attention {ph1[1]:.3f}")
 
     # the three-call step recorded once per resident layer into a HIP graph and replayed
     # (a side figure: a failure here must not cost the benchmark line)
     wallg_ms = None
     try:
+        if plain:
+            raise RuntimeError('--plain')
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         graphs = []
@@ -205,44 +209,46 @@ def run_workload(name, steps, warmup, layers, with_cpu, sample_rows, with_dense=
     # The attention kernel's two regimes on layer 0: the tile loop alone (the same index with its
     # diagonal lists emptied) against its MFMA roof, and what the diagonals add against the memory
     # roof (each (wave, diagonal) tile fetches 32 K rows and 32 V rows that nothing else uses).
-    Q, K, V, _ = resident[0]
-    ses.estimate(Q, K)
-    ses.build_index(ov)
-    c_full = ses.prefill_counted(Q, K, V, O)
-    saved_n_offs = ses.n_offs.clone()
+    attn_phases = None
+    if not plain:
+        Q, K, V, _ = resident[0]
+        ses.estimate(Q, K)
+        ses.build_index(ov)
+        c_full = ses.prefill_counted(Q, K, V, O)
+        saved_n_offs = ses.n_offs.clone()
 
-    def time_prefill(n=6):
-        for _ in range(2):
-            ses.prefill(Q, K, V, O)
-        a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a0.record()
-        for _ in range(n):
-            ses.prefill(Q, K, V, O)
-        a1.record()
-        torch.cuda.synchronize()
-        return a0.elapsed_time(a1) / n
+        def time_prefill(n=6):
+            for _ in range(2):
+                ses.prefill(Q, K, V, O)
+            a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a0.record()
+            for _ in range(n):
+                ses.prefill(Q, K, V, O)
+            a1.record()
+            torch.cuda.synchronize()
+            return a0.elapsed_time(a1) / n
 
-    t_full = time_prefill()
-    ses.n_offs.zero_()
-    c_tile = ses.prefill_counted(Q, K, V, O)
-    t_tile = time_prefill()
-    ses.n_offs.copy_(saved_n_offs)
-    diag_tiles = c_full[0] - c_tile[0]                 # one 32-key tile per (wave, diagonal)
-    diag_bytes = diag_tiles * 32 * 2 * d * 2           # 32 K rows + 32 V rows of d bf16 each
-    f_tile_loop = 4.0 * d * c_tile[0] * 32 * 32
-    t_diag = max(t_full - t_tile, 1e-6)
-    attn_phases = {
-        "layer": 0, "attention_ms": t_full,
-        "tile_loop": {"ms": t_tile, "flop_on_tiles": f_tile_loop, "TFLOPs_on_tiles": f_tile_loop / t_tile / 1e9,
-                      "frac_of_bf16_peak": f_tile_loop / t_tile / 1e9 / PEAK_BF16_TFLOPS,
-                      "how": "same index with n_offs = 0 (no diagonal phase)"},
-        "diagonals": {"ms": t_diag, "bytes": diag_bytes, "GBps": diag_bytes / t_diag / 1e6,
-                      "frac_of_hbm_peak": diag_bytes / t_diag / 1e6 / PEAK_HBM_GBS,
-                      "kept_pairs": c_full[1] - c_tile[1],
-                      "how": "difference to the full call; bytes = 32 K + 32 V rows per (wave, diagonal) tile"},
-    }
-    log(f"[{name}] attention {t_full:.3f} ms = tile loop {t_tile:.3f} ms ({attn_phases['tile_loop']['TFLOPs_on_tiles']:.0f} TFLOP/s on tiles) "
-        f"+ diagonals {t_diag:.3f} ms ({diag_bytes / 1e9:.2f} GB, {attn_phases['diagonals']['GBps']:.0f} GB/s)")
+        t_full = time_prefill()
+        ses.n_offs.zero_()
+        c_tile = ses.prefill_counted(Q, K, V, O)
+        t_tile = time_prefill()
+        ses.n_offs.copy_(saved_n_offs)
+        diag_tiles = c_full[0] - c_tile[0]                 # one 32-key tile per (wave, diagonal)
+        diag_bytes = diag_tiles * 32 * 2 * d * 2           # 32 K rows + 32 V rows of d bf16 each
+        f_tile_loop = 4.0 * d * c_tile[0] * 32 * 32
+        t_diag = max(t_full - t_tile, 1e-6)
+        attn_phases = {
+            "layer": 0, "attention_ms": t_full,
+            "tile_loop": {"ms": t_tile, "flop_on_tiles": f_tile_loop, "TFLOPs_on_tiles": f_tile_loop / t_tile / 1e9,
+                          "frac_of_bf16_peak": f_tile_loop / t_tile / 1e9 / PEAK_BF16_TFLOPS,
+                          "how": "same index with n_offs = 0 (no diagonal phase)"},
+            "diagonals": {"ms": t_diag, "bytes": diag_bytes, "GBps": diag_bytes / t_diag / 1e6,
+                          "frac_of_hbm_peak": diag_bytes / t_diag / 1e6 / PEAK_HBM_GBS,
+                          "kept_pairs": c_full[1] - c_tile[1],
+                          "how": "difference to the full call; bytes = 32 K + 32 V rows per (wave, diagonal) tile"},
+        }
+        log(f"[{name}] attention {t_full:.3f} ms = tile loop {t_tile:.3f} ms ({attn_phases['tile_loop']['TFLOPs_on_tiles']:.0f} TFLOP/s on tiles) "
+            f"+ diagonals {t_diag:.3f} ms ({diag_bytes / 1e9:.2f} GB, {attn_phases['diagonals']['GBps']:.0f} GB/s)")
     f_mask = 4.0 * d * float(np.mean(kept))
     f_tiles = 4.0 * d * float(np.mean(tiles)) * 32 * 32   # counter unit: one 32 x 32 sub-tile
     f_dense = 4.0 * d * Hq * N * (N + 1) / 2.0
@@ -250,8 +256,8 @@ def run_workload(name, steps, warmup, layers, with_cpu, sample_rows, with_dense=
     est_bytes = 2 * Hkv * N * d + 2 * Hq * N * d + 2 * Hq * w * d + 8 * Hq * N + 4 * Hq * nb * nb
     res = {
         "workload": name, "ms_per_step": wall_ms / steps, "prewarm_steps_untimed": n_pre,
-        "one_call_estimate_and_index": {"ms_per_step": wall1_ms / steps, "estimate_and_index": float(ph1[0]),
-                                        "attention": float(ph1[1])},
+        "one_call_estimate_and_index": None if plain else {"ms_per_step": wall1_ms / steps,
+                                                             "estimate_and_index": float(ph1[0]), "attention": float(ph1[1])},
         "graph_replay_ms_per_step": None if wallg_ms is None else wallg_ms / steps,
         "phases_ms": {"estimate": float(t_est), "index": float(t_idx), "attention": float(t_attn),
                       "attention_p95": float(np.percentile(ph[:, 2], 95))},
@@ -582,6 +588,9 @@ def main():
                     help="one-call form: compute the block map only for the heads decided Block-Cluster")
     ap.add_argument("--block-rules", action="store_true",
                     help="compare the two block rules (time, kept pairs, error against all-keys attention) instead")
+    ap.add_argument("--plain", action="store_true",
+                    help="run only the three-call loop and the work accounting (for kernel traces: the traced "
+                         "averages are then those of the timed steps)")
     ap.add_argument("--decode", action="store_true",
                     help="time one decode step over the prefill index of --workload instead")
     a = ap.parse_args()
@@ -623,7 +632,7 @@ def main():
     dsel = 1 if a.diagonals == "blocks" else 0
     main_res = run_workload(a.workload, a.steps, a.warmup, a.layers, not a.no_cpu_baseline, a.sample_rows,
                             block_select=bsel, diagonal_select=dsel, prewarm_s=a.prewarm,
-                            lazy_block_map=int(a.lazy_block_map), force_pattern=fpat)
+                            lazy_block_map=int(a.lazy_block_map), force_pattern=fpat, plain=a.plain)
     also = None
     if a.also and a.also != a.workload:
         also = run_workload(a.also, max(a.steps, 20), a.warmup, min(a.layers, 2), False, a.sample_rows,
