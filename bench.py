@@ -254,6 +254,20 @@ def run_workload(name, steps, warmup, layers, with_cpu, sample_rows, with_dense=
     f_dense = 4.0 * d * Hq * N * (N + 1) / 2.0
     nb = N // b
     est_bytes = 2 * Hkv * N * d + 2 * Hq * N * d + 2 * Hq * w * d + 8 * Hq * N + 4 * Hq * nb * nb
+    # what a plain device-to-device copy of 1 GiB moves on this machine (read + write): the rate a
+    # streaming kernel can be held against, beside the published peak
+    cs = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    cd = torch.empty_like(cs)
+    for _ in range(2):
+        cd.copy_(cs)
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(5):
+        cd.copy_(cs)
+    c1.record()
+    torch.cuda.synchronize()
+    copy_gbps = 2 * (1 << 30) * 5 / c0.elapsed_time(c1) / 1e6
+    del cs, cd
     res = {
         "workload": name, "ms_per_step": wall_ms / steps, "prewarm_steps_untimed": n_pre,
         "one_call_estimate_and_index": None if plain else {"ms_per_step": wall1_ms / steps,
@@ -267,7 +281,8 @@ def run_workload(name, steps, warmup, layers, with_cpu, sample_rows, with_dense=
         "kept_fraction_of_causal": float(np.mean(kept)) / (Hq * N * (N + 1) / 2.0),
         "mfma_frac_of_peak_on_tiles": f_tiles / t_attn / 1e9 / PEAK_BF16_TFLOPS,
         "estimator": {"algorithmic_bytes": est_bytes, "GBps": est_bytes / t_est / 1e6,
-                      "frac_of_hbm_peak": est_bytes / t_est / 1e6 / PEAK_HBM_GBS},
+                      "frac_of_hbm_peak": est_bytes / t_est / 1e6 / PEAK_HBM_GBS,
+                      "device_copy_GBps_same_run": copy_gbps},
         "attention_phases": attn_phases,
         "layer_sweep": sweep,
         "pattern_confusion_planted_x_chosen": confusion.tolist(),
