@@ -1,6 +1,7 @@
 """Pins for index selection (Alg. 2 TopK / CombineIndices, Alg. 3 TopKBlocks,
 the per-head pattern rule and the default budgets)."""
 import itertools
+import os
 
 import numpy as np
 import pytest
@@ -275,13 +276,18 @@ def test_triangular_csr_matches_definition():
 
 # ---- default budgets: the values of the benchmark definition's five shapes
 
-@pytest.mark.parametrize("N,b,rho,want", [
-    (4096, 64, 0.10, (208, 2, 128, 3)),
-    (16384, 64, 0.125, (4112, 15, 512, 16)),
-    (32768, 64, 0.06, (7880, 14, 512, 15)),
-    (65536, 128, 0.04, (5253, 9, 640, 20)),
-    (131072, 128, 0.03, (15744, 14, 960, 31)),
-])
+def _golden_budgets():
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "default_budgets.txt")
+    rows = []
+    for line in open(path):
+        if line.strip() and not line.startswith("#"):
+            f = line.split()
+            rows.append((int(f[0]), int(f[1]), float(f[2]), tuple(int(x) for x in f[3:7])))
+    assert len(rows) == 5
+    return rows
+
+
+@pytest.mark.parametrize("N,b,rho,want", _golden_budgets())
 def test_default_budgets_table(N, b, rho, want):
     bud = orc.default_budgets(N, b, rho)
     assert (bud.k_blocks, bud.local_blocks, bud.k_vertical, bud.k_slash) == want
