@@ -20,6 +20,9 @@ namespace sa {
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
@@ -329,6 +332,7 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
+  f32x4 lacc[2] = {};  // the tile loop's share of the normaliser (every register of a lane holds the same sum)
   unsigned st_kept = 0u, st_tiles = 0u;  // counted variant: this lane's kept pairs, this wave's sub-tiles
 
   // ---- global -> LDS pipeline -----------------------------------------------------------------
@@ -504,68 +508,84 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
     if (__any(m_new - m_run > 8.f)) {
       const float alpha = __builtin_amdgcn_exp2f(m_run - ((m_new == -INFINITY) ? 0.f : m_new));
       m_run = m_new;
-      l_run *= alpha;
+      lacc[0] *= alpha;
+      lacc[1] *= alpha;
 #pragma unroll
       for (int db = 0; db < 4; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
     }
     const float m_ref = (m_run == -INFINITY) ? 0.f : m_run;
-    float psum = 0.f;
     // Probabilities of key step g (8 of this lane's 32 entries, the B operand of that step's four
-    // MFMAs).  Step g + 1 is computed between the MFMAs of step g: vector-ALU and matrix
-    // instructions of one wave overlap only when they alternate in its instruction stream.
-    auto soft8 = [&](int g) {
+    // MFMAs), one pair at a time: exp2 of the pair j of step g, and its conversion to packed bf16.
+    auto soft2 = [&](int g, int j) {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[g >> 1][8 * (g & 1) + e], p.c, -m_ref));
-        sacc[g >> 1][8 * (g & 1) + e] = pe;
-        psum += pe;
-      }
+      for (int e = 2 * j; e < 2 * j + 2; ++e)
+        sacc[g >> 1][8 * (g & 1) + e] =
+            __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[g >> 1][8 * (g & 1) + e], p.c, -m_ref));
     };
-    soft8(0);
+    u32x4 pbuf[2];  // packed bf16 pairs of two consecutive steps
+    auto cvt2 = [&](int g, int j) {
+      const bf16x2 pr = {(__bf16)sacc[g >> 1][8 * (g & 1) + 2 * j], (__bf16)sacc[g >> 1][8 * (g & 1) + 2 * j + 1]};
+      pbuf[g & 1][j] = __builtin_bit_cast(uint32_t, pr);
+    };
+    // The normaliser sums the probabilities as the matrix pipe sees them, rounded to bf16: the weights
+    // p~ / sum p~ then add up to one exactly and a row's output stays a convex combination of its V
+    // rows whatever the rounding of the individual p (with an fp32 sum of the unrounded p, a row with
+    // a handful of kept keys shows the rounding of its dominant weight at full size).
+    // v_mfma_f32_4x4x4_16b_bf16 with an all-ones A operand leaves, in every output register of a
+    // lane, the sum of the four bf16 values the lane passed as B: two of them per key step
+    // (2 passes each) replace eight additions on the vector ALU.
+    const s16x4 ones4 = {0x3f80, 0x3f80, 0x3f80, 0x3f80};
     // ---- O^T += V^T P^T : k-slot (gg,e) of step (hf,u) <-> key 32hf + 16u + 8(e/4) + 4gg + e%4 ----
-    __builtin_amdgcn_s_setprio(1);
     const uint16_t *Vt = Vs[cur];
     {
       // 16 V^T fragments (4 key steps x 4 d blocks), each two transposing reads; same ring of four
       s16x4 vlo[4], vhi[4];
 #pragma unroll
+      for (int j = 0; j < 4; ++j) soft2(0, j);
+#pragma unroll
       for (int i = 0; i < 4; ++i) {
         vlo[i] = SA_VTR(Vt, i & 3, 16 * (i >> 2));
         vhi[i] = SA_VTR(Vt, i & 3, 16 * (i >> 2) + 8);
       }
-      bf16x8 pb;
+#pragma unroll
+      for (int j = 0; j < 3; ++j) cvt2(0, j);
+      __builtin_amdgcn_s_setprio(1);
+      // One slot per MFMA, in program order and fenced: the product, the two LDS reads that refill
+      // its V fragment, a quarter of the next step's exponentials and the conversion of the quarter
+      // before.  Vector-ALU and matrix instructions of one wave overlap only when they alternate
+      // in its instruction stream.
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const int g = i >> 2, db = i & 3;  // key step g = 2*hf + u covers keys 16g .. 16g+15
         if (db == 0) {
-#pragma unroll
-          for (int e = 0; e < 8; ++e) pb[e] = (__bf16)sacc[g >> 1][8 * (g & 1) + e];
-          if (g + 1 < 4) soft8(g + 1);
+          cvt2(g, 3);
+          asm("" : "+v"(pbuf[g & 1]));  // opaque from here on: halves are sub-registers, not new conversions
         }
+        const bf16x8 pb = __builtin_bit_cast(bf16x8, pbuf[g & 1]);
         const s16x8 av = __builtin_shufflevector(vlo[i & 3], vhi[i & 3], 0, 1, 2, 3, 4, 5, 6, 7);
         oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pb, oacc[db], 0, 0, 0);
+        {  // the step's row sums: low half in the first slot, high half in the last (placement swept: flat)
+          const s16x8 ps = __builtin_bit_cast(s16x8, pb);
+          if (db == 0)
+            lacc[0] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(ones4, __builtin_shufflevector(ps, ps, 0, 1, 2, 3), lacc[0], 0, 0, 0);
+          if (db == 3)
+            lacc[1] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(ones4, __builtin_shufflevector(ps, ps, 4, 5, 6, 7), lacc[1], 0, 0, 0);
+        }
         if (i + 4 < 16) {
           vlo[i & 3] = SA_VTR(Vt, (i + 4) & 3, 16 * ((i + 4) >> 2));
           vhi[i & 3] = SA_VTR(Vt, (i + 4) & 3, 16 * ((i + 4) >> 2) + 8);
         }
+        if (g + 1 < 4) {
+          soft2(g + 1, db);
+          if (db > 0) cvt2(g + 1, db - 1);
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
-      // order: the first step's probabilities and eight LDS reads; then per MFMA of the steps 0..2
-      // two LDS reads and a share of the next step's exp / add / convert work; then the last four
-      __builtin_amdgcn_sched_group_barrier(0x002, 24, 1);
-      __builtin_amdgcn_sched_group_barrier(0x100, 8, 1);
-      __builtin_amdgcn_sched_group_barrier(0x002, 4, 1);
-#pragma unroll
-      for (int i = 0; i < 12; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
-        __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
-        __builtin_amdgcn_sched_group_barrier(0x002, 7, 1);
-      }
-      __builtin_amdgcn_sched_group_barrier(0x008, 4, 1);
     }
-    l_run += psum;
   }
+  l_run = lacc[0][0] + lacc[1][0];
 
   // ---- selected diagonals: one 32-key tile per (wave, offset), no workgroup barriers -----------
   // For offset o the 32 queries of this wave need the 32 keys r0-o .. r0-o+31, and in
@@ -703,8 +723,8 @@ __global__ __launch_bounds__(256, 2) void sparse_prefill_kernel(AttnArgs p) {
       }
       const float m_ref = (m_run == -INFINITY) ? 0.f : m_run;
       const float pv = valid ? __builtin_amdgcn_exp2f(__builtin_fmaf(sv, p.c, -m_ref)) : 0.f;
-      l_run += pv;
       const __bf16 pvb = (__bf16)pv, zb = (__bf16)0.f;
+      l_run += (float)pvb;  // the weight as the matrix pipe sees it (see the tile loop's normaliser)
       // V of this offset has landed once only the 8 copies of the next K, issued after it, are
       // outstanding
       if (e_nxt < nd) __builtin_amdgcn_s_waitcnt(0x0F78);  // vmcnt(8)

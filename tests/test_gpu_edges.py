@@ -145,3 +145,43 @@ def test_head_counts_off_the_queue_grid(Hq, Hkv, N, b):
     assert_index_equal(ix, orc.build_index(v, s, blk, N, b, w, bud, override=ov))
     ref, _, _ = orc.masked_rows(Q, K, V, b, ix)
     check_attention(host_f64(Od), ref, f"heads {Hq}/{Hkv}")
+
+
+def test_rows_with_a_handful_of_keys_and_large_values():
+    # Rows that keep one to four keys, with V entries of magnitude 3.5 .. 4.4 planted in 6 % of V:
+    # the output is a convex combination of a few V rows, so the bf16 rounding of the dominant
+    # weight (2^-9 relative) shows at full size, 4.4 * 2^-9 = 0.009, on top of the output's own
+    # rounding (2^-6 at |O| in [4, 8)) unless the weights are normalised by the sum of what the
+    # matrix pipe actually multiplies.  Heads served by the diagonal phase only, by gather tiles
+    # only, and by both; no blocks at all.
+    print("case few-key rows", flush=True)
+    Hq, Hkv, N, b, w = 4, 2, 512, 128, 64
+    Q, K, V = gen.random_qkv(Hq, Hkv, N, 128, seed=2651)
+    rng = np.random.default_rng(77)
+    Vf = gen.bf16_bits_to_f32(V)
+    big = rng.random(Vf.shape) < 0.06
+    Vf[big] = (rng.uniform(3.5, 4.4, Vf.shape) * rng.choice([-1.0, 1.0], Vf.shape))[big].astype(np.float32)
+    V = gen.f32_to_bf16_bits(Vf)
+    k_v, k_s, nb = 4, 4, N // b
+    bud = orc.Budgets(1, 1, k_v, k_s, nb * (nb + 1) // 2 + nb)
+    ses = make_session(Hq, Hkv, N, b, w, bud)
+    cols = np.full((Hq, k_v), -1, np.int32)
+    offs = np.full((Hq, k_s), -1, np.int32)
+    want_offs = [[14, 233, 288, 505], [], [0, 1], [0, 130, 257]]
+    want_cols = [[], [3, 200, 410], [0], [5, 300]]
+    for h in range(Hq):
+        offs[h, :len(want_offs[h])] = want_offs[h]
+        cols[h, :len(want_cols[h])] = want_cols[h]
+    ix = orc.Index(np.array([1, 0, 1, 1], np.int32),
+                   np.array([len(c) for c in want_cols], np.int32), cols,
+                   np.array([len(o) for o in want_offs], np.int32), offs,
+                   np.zeros((Hq, nb + 1), np.int32), np.full((Hq, ses.cap_b), -1, np.int32))
+    upload_index(ses, ix)
+    Qd, Kd, Vd = dev_bf16(Q), dev_bf16(K), dev_bf16(V)
+    Od = torch.full_like(Qd, 7.0)
+    ses.prefill(Qd, Kd, Vd, Od)
+    torch.cuda.synchronize()
+    ref, _, kept = orc.masked_rows(Q, K, V, b, ix)
+    assert int(kept.max()) <= 5 and int((kept == 0).sum()) > 0  # a handful of keys; some rows keep none
+    assert float(np.abs(ref).max()) > 4.0                       # and the case does reach the large outputs
+    check_attention(host_f64(Od), ref, "few-key rows")
